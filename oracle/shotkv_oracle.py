@@ -274,12 +274,11 @@ def decode_step(k_prefill, v_prefill, prefill_count, k_dec, v_dec, slot_pos, dec
     scores = np.zeros(n_slots)
     for h in range(H):
         g = h // G
-        keys = np.concatenate([kp[g, :pc], kd[g, occ]], axis=0)
-        vals = np.concatenate([vp[g, :pc], vd[g, occ]], axis=0)
-        z = float(sm_scale) * (keys @ q[h])
+        # logits over the union [live prefill rows | occupied decode slots], one softmax over both
+        z = float(sm_scale) * np.concatenate([kp[g, :pc] @ q[h], kd[g, occ] @ q[h]])
         e = np.exp(z - z.max())
         w = e / e.sum()
-        res["out"][h] = w @ vals
+        res["out"][h] = w[:pc] @ vp[g, :pc] + w[pc:] @ vd[g, occ]
         scores[occ] += w[pc:]
     res["token_scores"] = scores
     res["margin"] = eviction_margin(scores, slot_pos, f)

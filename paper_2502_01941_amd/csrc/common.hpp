@@ -1,0 +1,169 @@
+// Shared device/host helpers for the ShotKV gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "shotkv.h"
+
+namespace shotkv {
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+
+// Keys per scoring chunk.  A chunk never straddles a shot boundary, so a chunk's softmax partial can
+// be credited to exactly one shot (or to the always-kept region).
+constexpr int kChunkKeys = 256;       // MFMA path: one wave walks a chunk in 32-key blocks
+constexpr int kChunkKeysGeneric = 64; // generic path: one 64-key block per workgroup
+
+typedef uint16_t bf16_t;  // raw bf16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) {
+  return __uint_as_float(static_cast<uint32_t>(x) << 16);
+}
+__device__ __forceinline__ float to_f32(bf16_t x) { return bf16_to_f32(x); }
+__device__ __forceinline__ float to_f32(float x) { return x; }
+
+template <typename T>
+__device__ __forceinline__ T wave_max(T v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+__host__ __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Upper bound on the number of chunks one problem can be cut into: every segment (n_shots shots plus
+// the prefix and tail regions) adds at most one partially filled chunk.
+__host__ __device__ __forceinline__ int max_chunks(int n_tokens, int n_shots, int chunk_keys) {
+  return ceil_div(n_tokens, chunk_keys) + n_shots + 2;
+}
+
+// ---- workspace carving (host) -------------------------------------------------------------------
+
+struct PrefillWorkspace {
+  // chunk table, one row per problem
+  int32_t* n_chunks;      // [P]
+  int32_t* chunk_start;   // [P][maxC] first key of the chunk
+  int32_t* chunk_len;     // [P][maxC] keys in the chunk (<= chunk_keys)
+  int32_t* seg_first;     // [P][n_shots+3] first chunk of segment s; segment 0 = prefix, 1..n = shots,
+                          //                n+1 = tail, entry n+2 = n_chunks
+  // softmax partials per (problem, kv head, chunk, row): running max (log2 domain) and sum
+  float2*  partial;       // [P][H_kv][maxC][R]
+  float2*  row_stat;      // [P][H_kv][R]  (global max, 1 / global sum)
+  float*   chunk_mass;    // [P][maxC]
+  float*   scores;        // [P][n_shots]
+  // copy plan
+  int32_t* n_runs;        // [P]
+  int32_t* run_src;       // [P][n_shots+2]
+  int32_t* run_dst;       // [P][n_shots+2]
+  int32_t* run_len;       // [P][n_shots+2]
+  int32_t  max_c;
+  int32_t  chunk_keys;
+  size_t   bytes;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_tokens, int n_shots,
+                                      int chunk_keys) {
+  PrefillWorkspace w{};
+  w.chunk_keys = chunk_keys;
+  w.max_c = max_chunks(n_tokens, n_shots, chunk_keys);
+  size_t off = 0;
+  char* b = static_cast<char*>(base);
+  auto take = [&](size_t bytes) {
+    char* p = b ? b + off : nullptr;
+    off = align_up(off + bytes, 256);
+    return p;
+  };
+  const size_t P_ = P, C = w.max_c, S = n_shots;
+  w.n_chunks = reinterpret_cast<int32_t*>(take(P_ * 4));
+  w.chunk_start = reinterpret_cast<int32_t*>(take(P_ * C * 4));
+  w.chunk_len = reinterpret_cast<int32_t*>(take(P_ * C * 4));
+  w.seg_first = reinterpret_cast<int32_t*>(take(P_ * (S + 3) * 4));
+  w.partial = reinterpret_cast<float2*>(take(P_ * H_kv * C * R * 8));
+  w.row_stat = reinterpret_cast<float2*>(take(P_ * H_kv * R * 8));
+  w.chunk_mass = reinterpret_cast<float*>(take(P_ * C * 4));
+  w.scores = reinterpret_cast<float*>(take(P_ * S * 4 + 4));
+  w.n_runs = reinterpret_cast<int32_t*>(take(P_ * 4));
+  w.run_src = reinterpret_cast<int32_t*>(take(P_ * (S + 2) * 4));
+  w.run_dst = reinterpret_cast<int32_t*>(take(P_ * (S + 2) * 4));
+  w.run_len = reinterpret_cast<int32_t*>(take(P_ * (S + 2) * 4));
+  w.bytes = off;
+  return w;
+}
+
+// ---- launchers implemented in the kernel files --------------------------------------------------
+
+struct PrefillDims {
+  int P, n_tokens, n_shots, H, H_kv, G, D, W, R;  // R = G * W rows per KV head
+  int dtype;
+  float sm_scale;
+  int select_mode;
+};
+
+hipError_t launch_plan_chunks(const PrefillDims& d, const int32_t* shot_offsets, int32_t* status,
+                              const PrefillWorkspace& w, hipStream_t s);
+hipError_t launch_score_partials(const PrefillDims& d, const void* q_obs, const void* k,
+                                 const PrefillWorkspace& w, hipStream_t s);
+hipError_t launch_reduce_scores(const PrefillDims& d, const int32_t* shot_offsets,
+                                const int32_t* status, float* shot_scores, const PrefillWorkspace& w,
+                                hipStream_t s);
+hipError_t launch_select_plan(const PrefillDims& d, const float* shot_scores,
+                              const int32_t* shot_offsets, const int32_t* budget_tokens, int cap,
+                              int32_t* kept_count, uint8_t* shot_selected, int32_t* status,
+                              const PrefillWorkspace& w, hipStream_t s);
+hipError_t launch_compact(const PrefillDims& d, const void* k, const void* v, void* k_out, void* v_out,
+                          int cap, int32_t* kept_positions, const int32_t* kept_count,
+                          const PrefillWorkspace& w, hipStream_t s);
+
+bool score_uses_mfma(const PrefillDims& d);
+
+struct DecodeDims {
+  int S, H, H_kv, G, D, dtype, cap, n_slots, budget, step, n_splits, split_tokens;
+  float sm_scale;
+};
+
+struct DecodeWorkspace {
+  float2* part_ml;   // [S][H][n_splits] (max in log2 domain, sum)
+  float*  part_o;    // [S][H][n_splits][D]
+  float*  z_dec;     // [S][H][n_slots] scaled logits (log2 domain) of decode slots, -inf when free
+  int32_t* new_slot; // [S]
+  size_t  bytes;
+};
+
+inline DecodeWorkspace carve_decode(void* base, int S, int H, int D, int n_slots, int n_splits) {
+  DecodeWorkspace w{};
+  size_t off = 0;
+  char* b = static_cast<char*>(base);
+  auto take = [&](size_t bytes) {
+    char* p = b ? b + off : nullptr;
+    off = align_up(off + bytes, 256);
+    return p;
+  };
+  const size_t S_ = S;
+  w.part_ml = reinterpret_cast<float2*>(take(S_ * H * n_splits * 8));
+  w.part_o = reinterpret_cast<float*>(take(S_ * H * n_splits * D * 4));
+  w.z_dec = reinterpret_cast<float*>(take(S_ * H * n_slots * 4));
+  w.new_slot = reinterpret_cast<int32_t*>(take(S_ * 4));
+  w.bytes = off;
+  return w;
+}
+
+int decode_splits(int S, int H_kv, int total_tokens);
+
+hipError_t launch_decode_partial(const DecodeDims& d, const shotkv_decode_state& st, const void* q_new,
+                                 const void* k_new, const void* v_new, const DecodeWorkspace& w,
+                                 hipStream_t s);
+hipError_t launch_decode_finish(const DecodeDims& d, const shotkv_decode_state& st, float* out,
+                                float* token_scores, int32_t* evicted_pos, int32_t* status,
+                                const DecodeWorkspace& w, hipStream_t s);
+
+}  // namespace shotkv

@@ -1,0 +1,116 @@
+// Chunk planning for the prefill score pass (Section 5.1, Eq. 3: shots are the pooling units).
+//
+// The key range [0, n_tokens) of a problem is cut into segments - the region before the first shot,
+// each shot, the region after the last shot - and every segment into chunks of at most chunk_keys
+// keys.  Because a chunk never crosses a shot boundary, the score pass needs no per-key segment
+// bookkeeping: a chunk's softmax partial belongs to one shot or to the always-kept region.
+#include "common.hpp"
+
+namespace shotkv {
+
+namespace {
+
+constexpr int kPlanThreads = 256;
+
+__device__ __forceinline__ void segment_span(const int32_t* off, int n_shots, int n_tokens, int s,
+                                             int& start, int& len) {
+  // s = 0: prefix, 1..n: shots, n+1: tail
+  const int lo = (s == 0) ? 0 : off[s - 1];
+  const int hi = (s == n_shots + 1) ? n_tokens : off[s];
+  start = lo;
+  len = hi - lo;
+}
+
+__device__ __forceinline__ int chunks_of(int len, int chunk_keys) {
+  return len <= 0 ? 0 : (len + chunk_keys - 1) / chunk_keys;
+}
+
+__device__ __forceinline__ int chunk_stride(int len, int nc) {
+  // equal split rounded up to whole 32-key blocks; never more than chunk_keys because
+  // len <= nc * chunk_keys and chunk_keys is a multiple of 32
+  const int per = (len + nc - 1) / nc;
+  return (per + 31) & ~31;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
+    const int32_t* __restrict__ shot_offsets, int n_shots, int n_tokens, int chunk_keys, int max_c,
+    int32_t* __restrict__ status, int32_t* __restrict__ n_chunks, int32_t* __restrict__ chunk_start,
+    int32_t* __restrict__ chunk_len, int32_t* __restrict__ seg_first) {
+  const int p = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int32_t* off = shot_offsets + static_cast<size_t>(p) * (n_shots + 1);
+  int32_t* c_start = chunk_start + static_cast<size_t>(p) * max_c;
+  int32_t* c_len = chunk_len + static_cast<size_t>(p) * max_c;
+  int32_t* s_first = seg_first + static_cast<size_t>(p) * (n_shots + 3);
+
+  __shared__ int bad;
+  __shared__ int scan[kPlanThreads];
+  __shared__ int carry;
+  if (tid == 0) { bad = 0; carry = 0; }
+  __syncthreads();
+
+  // validation: 0 <= off[0], off strictly increasing, off[n] <= n_tokens
+  int local_bad = 0;
+  for (int i = tid; i <= n_shots; i += kPlanThreads) {
+    const int o = off[i];
+    if (o < 0 || o > n_tokens) local_bad = 1;
+    if (i > 0 && o <= off[i - 1]) local_bad = 1;
+  }
+  if (local_bad) atomicOr(&bad, 1);
+  __syncthreads();
+  if (bad) {
+    if (tid == 0) { status[p] = SHOTKV_ST_BAD_OFFSETS; n_chunks[p] = 0; }
+    for (int s = tid; s < n_shots + 3; s += kPlanThreads) s_first[s] = 0;
+    return;
+  }
+  if (tid == 0) status[p] = SHOTKV_ST_OK;
+
+  const int n_seg = n_shots + 2;
+  for (int base = 0; base < n_seg; base += kPlanThreads) {
+    const int s = base + tid;
+    int start = 0, len = 0, nc = 0;
+    if (s < n_seg) {
+      segment_span(off, n_shots, n_tokens, s, start, len);
+      nc = chunks_of(len, chunk_keys);
+    }
+    // inclusive Hillis-Steele scan of nc over the tile
+    scan[tid] = nc;
+    __syncthreads();
+    for (int o = 1; o < kPlanThreads; o <<= 1) {
+      const int add = (tid >= o) ? scan[tid - o] : 0;
+      __syncthreads();
+      scan[tid] += add;
+      __syncthreads();
+    }
+    const int first = carry + scan[tid] - nc;
+    if (s < n_seg) {
+      s_first[s] = first;
+      if (nc > 0) {
+        const int per = chunk_stride(len, nc);
+        for (int j = 0; j < nc; ++j) {
+          c_start[first + j] = start + j * per;
+          c_len[first + j] = min(per, len - j * per);
+        }
+      }
+    }
+    __syncthreads();
+    if (tid == kPlanThreads - 1) carry += scan[tid];
+    __syncthreads();
+  }
+  if (tid == 0) {
+    s_first[n_seg] = carry;
+    n_chunks[p] = carry;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_plan_chunks(const PrefillDims& d, const int32_t* shot_offsets, int32_t* status,
+                              const PrefillWorkspace& w, hipStream_t s) {
+  hipLaunchKernelGGL(plan_chunks_kernel, dim3(d.P), dim3(kPlanThreads), 0, s, shot_offsets, d.n_shots,
+                     d.n_tokens, w.chunk_keys, w.max_c, status, w.n_chunks, w.chunk_start, w.chunk_len,
+                     w.seg_first);
+  return hipGetLastError();
+}
+
+}  // namespace shotkv

@@ -1,0 +1,118 @@
+// Segmented per-shot reduction of the softmax partials (Section 5.1, Eq. 3).
+//
+//   row_stats   : per (problem, KV head, query row) the global max M and 1/L over all chunks
+//   chunk_mass  : per (problem, chunk) the attention mass sum_{heads, rows} l * 2^(m - M) / L
+//   shot_scores : Score(s_i) = (sum of the masses of the shot's chunks) / k_i
+// All sums are in fixed order (no atomics), so results are reproducible run to run.
+#include "common.hpp"
+
+namespace shotkv {
+
+namespace {
+
+constexpr int kStatThreads = 1024;
+
+__global__ __launch_bounds__(kStatThreads) void row_stats_kernel(const float2* __restrict__ partial,
+                                                                 const int32_t* __restrict__ n_chunks,
+                                                                 int H_kv, int R, int max_c,
+                                                                 float2* __restrict__ row_stat) {
+  const int g = blockIdx.x, p = blockIdx.y;
+  const int nl = kStatThreads / R;  // chunk lanes
+  const int tid = threadIdx.x;
+  const int r = tid % R, cl = tid / R;
+  const int nc = n_chunks[p];
+  const float2* base = partial + (static_cast<size_t>(p) * H_kv + g) * max_c * R;
+  float M = -INFINITY, L = 0.f;
+  if (cl < nl) {
+    for (int c = cl; c < nc; c += nl) {
+      const float2 ml = base[static_cast<size_t>(c) * R + r];
+      if (ml.y > 0.f) {
+        const float Mn = fmaxf(M, ml.x);
+        L = L * exp2f(M - Mn) + ml.y * exp2f(ml.x - Mn);
+        M = Mn;
+      }
+    }
+  }
+  __shared__ float sM[kStatThreads];
+  __shared__ float sL[kStatThreads];
+  sM[tid] = M;
+  sL[tid] = L;
+  __syncthreads();
+  if (tid < R) {
+    float Mt = -INFINITY, Lt = 0.f;
+    for (int i = 0; i < nl; ++i) {
+      const float m = sM[i * R + tid], l = sL[i * R + tid];
+      if (l > 0.f) {
+        const float Mn = fmaxf(Mt, m);
+        Lt = Lt * exp2f(Mt - Mn) + l * exp2f(m - Mn);
+        Mt = Mn;
+      }
+    }
+    row_stat[(static_cast<size_t>(p) * H_kv + g) * R + tid] =
+        make_float2(Mt, Lt > 0.f ? 1.f / Lt : 0.f);
+  }
+}
+
+constexpr int kMassThreads = 256;
+
+__global__ __launch_bounds__(kMassThreads) void chunk_mass_kernel(const float2* __restrict__ partial,
+                                                                  const float2* __restrict__ row_stat,
+                                                                  const int32_t* __restrict__ n_chunks,
+                                                                  int H_kv, int R, int max_c,
+                                                                  float* __restrict__ chunk_mass) {
+  const int p = blockIdx.y;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int c = blockIdx.x * (kMassThreads / kWave) + wave;
+  if (c >= n_chunks[p]) return;
+  const float2* stat = row_stat + static_cast<size_t>(p) * H_kv * R;
+  float acc = 0.f;
+  for (int g = 0; g < H_kv; ++g) {
+    const float2* part = partial + ((static_cast<size_t>(p) * H_kv + g) * max_c + c) * R;
+    for (int r = lane; r < R; r += kWave) {
+      const float2 ml = part[r];
+      const float2 st = stat[g * R + r];
+      if (ml.y > 0.f) acc += ml.y * exp2f(ml.x - st.x) * st.y;
+    }
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) chunk_mass[static_cast<size_t>(p) * max_c + c] = acc;
+}
+
+__global__ void shot_scores_kernel(const float* __restrict__ chunk_mass,
+                                   const int32_t* __restrict__ seg_first,
+                                   const int32_t* __restrict__ shot_offsets,
+                                   const int32_t* __restrict__ status, int n_shots, int max_c,
+                                   float* __restrict__ shot_scores) {
+  const int p = blockIdx.y;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_shots) return;
+  float score = 0.f;
+  if (status[p] == SHOTKV_ST_OK) {
+    const int32_t* sf = seg_first + static_cast<size_t>(p) * (n_shots + 3);
+    const int32_t* off = shot_offsets + static_cast<size_t>(p) * (n_shots + 1);
+    const float* mass = chunk_mass + static_cast<size_t>(p) * max_c;
+    float sum = 0.f;
+    for (int c = sf[i + 1]; c < sf[i + 2]; ++c) sum += mass[c];
+    score = sum / static_cast<float>(off[i + 1] - off[i]);
+  }
+  shot_scores[static_cast<size_t>(p) * n_shots + i] = score;
+}
+
+}  // namespace
+
+hipError_t launch_reduce_scores(const PrefillDims& d, const int32_t* shot_offsets,
+                                const int32_t* status, float* shot_scores, const PrefillWorkspace& w,
+                                hipStream_t s) {
+  hipLaunchKernelGGL(row_stats_kernel, dim3(d.H_kv, d.P), dim3(kStatThreads), 0, s, w.partial,
+                     w.n_chunks, d.H_kv, d.R, w.max_c, w.row_stat);
+  hipLaunchKernelGGL(chunk_mass_kernel, dim3(ceil_div(w.max_c, kMassThreads / kWave), d.P),
+                     dim3(kMassThreads), 0, s, w.partial, w.row_stat, w.n_chunks, d.H_kv, d.R, w.max_c,
+                     w.chunk_mass);
+  if (d.n_shots > 0) {
+    hipLaunchKernelGGL(shot_scores_kernel, dim3(ceil_div(d.n_shots, 256), d.P), dim3(256), 0, s,
+                       w.chunk_mass, w.seg_first, shot_offsets, status, d.n_shots, w.max_c, shot_scores);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace shotkv

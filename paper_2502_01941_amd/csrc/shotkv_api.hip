@@ -1,0 +1,203 @@
+// C ABI of the ShotKV library: argument checks, workspace carving and kernel sequencing.
+// Every entry point only enqueues work on the caller's stream.
+#include "common.hpp"
+
+namespace shotkv {
+
+hipError_t launch_score_partials_generic(const PrefillDims& d, const void* q_obs, const void* k,
+                                         const PrefillWorkspace& w, hipStream_t s);
+hipError_t launch_score_partials_mfma(const PrefillDims& d, const void* q_obs, const void* k,
+                                      const PrefillWorkspace& w, hipStream_t s);
+
+hipError_t launch_score_partials(const PrefillDims& d, const void* q_obs, const void* k,
+                                 const PrefillWorkspace& w, hipStream_t s) {
+  return score_uses_mfma(d) ? launch_score_partials_mfma(d, q_obs, k, w, s)
+                            : launch_score_partials_generic(d, q_obs, k, w, s);
+}
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_config(const shotkv_config* cfg) {
+  if (!cfg) return SHOTKV_E_NULL;
+  if (cfg->dtype != SHOTKV_BF16 && cfg->dtype != SHOTKV_F32) return SHOTKV_E_SHAPE;
+  if (cfg->head_dim != 64 && cfg->head_dim != 128) return SHOTKV_E_SHAPE;
+  if (cfg->n_kv_heads < 1 || cfg->n_q_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads) return SHOTKV_E_SHAPE;
+  const int G = cfg->n_q_heads / cfg->n_kv_heads;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return SHOTKV_E_SHAPE;
+  if (cfg->n_q_heads > 64) return SHOTKV_E_SHAPE;
+  if (cfg->select_mode != SHOTKV_SELECT_PREFIX && cfg->select_mode != SHOTKV_SELECT_FIRST_FIT)
+    return SHOTKV_E_SHAPE;
+  if (!(cfg->sm_scale > 0.f)) return SHOTKV_E_SHAPE;
+  return SHOTKV_OK;
+}
+
+int make_prefill_dims(const shotkv_config* cfg, int P, int n_tokens, int n_shots, PrefillDims* d) {
+  const int rc = check_config(cfg);
+  if (rc != SHOTKV_OK) return rc;
+  if (cfg->window < 1 || cfg->window > 64) return SHOTKV_E_SHAPE;
+  const int G = cfg->n_q_heads / cfg->n_kv_heads;
+  if (G * cfg->window > 256) return SHOTKV_E_SHAPE;
+  if (P < 1 || P > 32767 || n_tokens < cfg->window || n_shots < 0 || n_shots > SHOTKV_MAX_SHOTS)
+    return SHOTKV_E_SHAPE;
+  d->P = P; d->n_tokens = n_tokens; d->n_shots = n_shots;
+  d->H = cfg->n_q_heads; d->H_kv = cfg->n_kv_heads; d->G = G; d->D = cfg->head_dim;
+  d->W = cfg->window; d->R = G * cfg->window; d->dtype = cfg->dtype; d->sm_scale = cfg->sm_scale;
+  d->select_mode = cfg->select_mode;
+  return SHOTKV_OK;
+}
+
+PrefillWorkspace carve(const PrefillDims& d, void* base) {
+  return carve_prefill(base, d.P, d.H_kv, d.R, d.n_tokens, d.n_shots,
+                       score_uses_mfma(d) ? kChunkKeys : kChunkKeysGeneric);
+}
+
+int from_hip(hipError_t e) { return e == hipSuccess ? SHOTKV_OK : SHOTKV_E_LAUNCH; }
+
+}  // namespace
+}  // namespace shotkv
+
+using namespace shotkv;
+
+extern "C" {
+
+const char* shotkv_strerror(int code) {
+  switch (code) {
+    case SHOTKV_OK: return "ok";
+    case SHOTKV_E_NULL: return "required pointer is NULL";
+    case SHOTKV_E_SHAPE: return "unsupported or inconsistent shape, dtype or mode";
+    case SHOTKV_E_WORKSPACE: return "workspace too small";
+    case SHOTKV_E_ALIGN: return "tensor pointer not 16-byte aligned";
+    case SHOTKV_E_LAUNCH: return "HIP launch failed";
+    default: return "unknown shotkv error";
+  }
+}
+
+int32_t shotkv_abi_version(void) { return 1; }
+
+size_t shotkv_prefill_workspace_bytes(const shotkv_config* cfg, int32_t P, int32_t n_tokens,
+                                      int32_t n_shots) {
+  PrefillDims d;
+  if (make_prefill_dims(cfg, P, n_tokens, n_shots, &d) != SHOTKV_OK) return 0;
+  return carve(d, nullptr).bytes;
+}
+
+int shotkv_prefill_scores(const shotkv_config* cfg, int32_t P, int32_t n_tokens, int32_t n_shots,
+                          const void* q_obs, const void* k, const int32_t* shot_offsets,
+                          float* shot_scores, int32_t* status, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  PrefillDims d;
+  const int rc = make_prefill_dims(cfg, P, n_tokens, n_shots, &d);
+  if (rc != SHOTKV_OK) return rc;
+  if (!q_obs || !k || !shot_offsets || !shot_scores || !status || !workspace) return SHOTKV_E_NULL;
+  if (!aligned16(q_obs) || !aligned16(k) || !aligned16(workspace)) return SHOTKV_E_ALIGN;
+  const PrefillWorkspace w = carve(d, workspace);
+  if (workspace_bytes < w.bytes) return SHOTKV_E_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_plan_chunks(d, shot_offsets, status, w, s);
+  if (e == hipSuccess) e = launch_score_partials(d, q_obs, k, w, s);
+  if (e == hipSuccess) e = launch_reduce_scores(d, shot_offsets, status, shot_scores, w, s);
+  return from_hip(e);
+}
+
+int shotkv_select_and_compact(const shotkv_config* cfg, int32_t P, int32_t n_tokens, int32_t n_shots,
+                              const float* shot_scores, const void* k, const void* v,
+                              const int32_t* shot_offsets, const int32_t* budget_tokens, void* k_out,
+                              void* v_out, int32_t cap, int32_t* kept_positions, int32_t* kept_count,
+                              uint8_t* shot_selected, int32_t* status, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  PrefillDims d;
+  const int rc = make_prefill_dims(cfg, P, n_tokens, n_shots, &d);
+  if (rc != SHOTKV_OK) return rc;
+  if (cap < 1) return SHOTKV_E_SHAPE;
+  if (!k || !v || !shot_offsets || !budget_tokens || !k_out || !v_out || !kept_positions ||
+      !kept_count || !status || !workspace || (n_shots > 0 && !shot_scores))
+    return SHOTKV_E_NULL;
+  if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out) || !aligned16(workspace))
+    return SHOTKV_E_ALIGN;
+  const PrefillWorkspace w = carve(d, workspace);
+  if (workspace_bytes < w.bytes) return SHOTKV_E_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_select_plan(d, shot_scores, shot_offsets, budget_tokens, cap, kept_count,
+                                    shot_selected, status, w, s);
+  if (e == hipSuccess) e = launch_compact(d, k, v, k_out, v_out, cap, kept_positions, kept_count, w, s);
+  return from_hip(e);
+}
+
+int shotkv_prefill_compress(const shotkv_config* cfg, int32_t P, int32_t n_tokens, int32_t n_shots,
+                            const void* q_obs, const void* k, const void* v,
+                            const int32_t* shot_offsets, const int32_t* budget_tokens, void* k_out,
+                            void* v_out, int32_t cap, int32_t* kept_positions, int32_t* kept_count,
+                            float* shot_scores, uint8_t* shot_selected, int32_t* status,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+  PrefillDims d;
+  const int rc = make_prefill_dims(cfg, P, n_tokens, n_shots, &d);
+  if (rc != SHOTKV_OK) return rc;
+  if (cap < 1) return SHOTKV_E_SHAPE;
+  if (!q_obs || !k || !v || !shot_offsets || !budget_tokens || !k_out || !v_out || !kept_positions ||
+      !kept_count || !status || !workspace)
+    return SHOTKV_E_NULL;
+  if (!aligned16(q_obs) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out) ||
+      !aligned16(workspace))
+    return SHOTKV_E_ALIGN;
+  const PrefillWorkspace w = carve(d, workspace);
+  if (workspace_bytes < w.bytes) return SHOTKV_E_WORKSPACE;
+  float* scores = shot_scores ? shot_scores : w.scores;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_plan_chunks(d, shot_offsets, status, w, s);
+  if (e == hipSuccess) e = launch_score_partials(d, q_obs, k, w, s);
+  if (e == hipSuccess) e = launch_reduce_scores(d, shot_offsets, status, scores, w, s);
+  if (e == hipSuccess)
+    e = launch_select_plan(d, scores, shot_offsets, budget_tokens, cap, kept_count, shot_selected,
+                           status, w, s);
+  if (e == hipSuccess) e = launch_compact(d, k, v, k_out, v_out, cap, kept_positions, kept_count, w, s);
+  return from_hip(e);
+}
+
+static int make_decode_dims(const shotkv_config* cfg, int S, int cap, int n_slots, DecodeDims* d) {
+  const int rc = check_config(cfg);
+  if (rc != SHOTKV_OK) return rc;
+  if (S < 1 || S > 65535 || cap < 0 || n_slots < 1) return SHOTKV_E_SHAPE;
+  d->S = S; d->H = cfg->n_q_heads; d->H_kv = cfg->n_kv_heads; d->G = d->H / d->H_kv;
+  d->D = cfg->head_dim; d->dtype = cfg->dtype; d->cap = cap; d->n_slots = n_slots;
+  d->sm_scale = cfg->sm_scale;
+  const int total = cap + n_slots;
+  d->n_splits = decode_splits(S, d->H_kv, total);
+  d->split_tokens = ceil_div(total, d->n_splits);
+  return SHOTKV_OK;
+}
+
+size_t shotkv_decode_workspace_bytes(const shotkv_config* cfg, int32_t S, int32_t cap, int32_t n_slots) {
+  DecodeDims d;
+  if (make_decode_dims(cfg, S, cap, n_slots, &d) != SHOTKV_OK) return 0;
+  return carve_decode(nullptr, d.S, d.H, d.D, d.n_slots, d.n_splits).bytes;
+}
+
+int shotkv_decode_step(const shotkv_config* cfg, int32_t S, const shotkv_decode_state* st,
+                       int32_t step_index, const void* q_new, const void* k_new, const void* v_new,
+                       float* out, float* token_scores, int32_t* evicted_pos, int32_t* status,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (!st) return SHOTKV_E_NULL;
+  DecodeDims d;
+  const int rc = make_decode_dims(cfg, S, st->cap, st->n_slots, &d);
+  if (rc != SHOTKV_OK) return rc;
+  if (st->decode_budget < 1 || step_index < 0) return SHOTKV_E_SHAPE;
+  if (!st->prefill_count || !st->k_dec || !st->v_dec || !st->slot_pos || !q_new || !k_new || !v_new ||
+      !out || !status || !workspace || (st->cap > 0 && (!st->k_prefill || !st->v_prefill)))
+    return SHOTKV_E_NULL;
+  if (!aligned16(st->k_prefill) || !aligned16(st->v_prefill) || !aligned16(st->k_dec) ||
+      !aligned16(st->v_dec) || !aligned16(q_new) || !aligned16(k_new) || !aligned16(v_new) ||
+      !aligned16(workspace))
+    return SHOTKV_E_ALIGN;
+  const DecodeWorkspace w = carve_decode(workspace, d.S, d.H, d.D, d.n_slots, d.n_splits);
+  if (workspace_bytes < w.bytes) return SHOTKV_E_WORKSPACE;
+  d.budget = st->decode_budget;
+  d.step = step_index;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_decode_partial(d, *st, q_new, k_new, v_new, w, s);
+  if (e == hipSuccess) e = launch_decode_finish(d, *st, out, token_scores, evicted_pos, status, w, s);
+  return from_hip(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,271 @@
+"""Thin ctypes binding over libshotkv.so (the C ABI declared in include/shotkv.h).
+
+Argument marshalling only: every step of the method runs in the library's HIP kernels.  PyTorch is
+used for device memory and for the current HIP stream.  There is no fallback: if the library has not
+been built (python -m paper_2502_01941_amd.build) loading fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import dataclasses
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libshotkv.so")
+
+BF16, F32 = 0, 1
+SELECT_PREFIX, SELECT_FIRST_FIT = 0, 1
+ST_OK, ST_BAD_OFFSETS, ST_BUDGET_TOO_SMALL, ST_NO_FREE_SLOT = 0, -1, -2, -3
+INT32_MAX = 2 ** 31 - 1
+
+EXPORTS = (
+    "shotkv_strerror", "shotkv_abi_version", "shotkv_prefill_workspace_bytes",
+    "shotkv_prefill_compress", "shotkv_prefill_scores", "shotkv_select_and_compact",
+    "shotkv_decode_workspace_bytes", "shotkv_decode_step",
+)
+
+
+class ShotKVError(RuntimeError):
+    pass
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("window", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("sm_scale", ctypes.c_float), ("select_mode", ctypes.c_int32)]
+
+
+class _DecodeState(ctypes.Structure):
+    _fields_ = [("k_prefill", ctypes.c_void_p), ("v_prefill", ctypes.c_void_p),
+                ("prefill_count", ctypes.c_void_p), ("k_dec", ctypes.c_void_p),
+                ("v_dec", ctypes.c_void_p), ("slot_pos", ctypes.c_void_p), ("cap", ctypes.c_int32),
+                ("n_slots", ctypes.c_int32), ("decode_budget", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libshotkv.so and declare the prototypes.  Raises if the library is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ShotKVError(f"{LIB_PATH} not found: build it with `python -m paper_2502_01941_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    cfgp = ctypes.POINTER(_Config)
+    lib.shotkv_strerror.restype = ctypes.c_char_p
+    lib.shotkv_strerror.argtypes = [ctypes.c_int]
+    lib.shotkv_abi_version.restype = i32
+    lib.shotkv_abi_version.argtypes = []
+    lib.shotkv_prefill_workspace_bytes.restype = sz
+    lib.shotkv_prefill_workspace_bytes.argtypes = [cfgp, i32, i32, i32]
+    lib.shotkv_prefill_compress.restype = ctypes.c_int
+    lib.shotkv_prefill_compress.argtypes = [cfgp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp,
+                                            vp, vp, vp, vp, sz, vp]
+    lib.shotkv_prefill_scores.restype = ctypes.c_int
+    lib.shotkv_prefill_scores.argtypes = [cfgp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.shotkv_select_and_compact.restype = ctypes.c_int
+    lib.shotkv_select_and_compact.argtypes = [cfgp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp,
+                                              vp, vp, vp, vp, sz, vp]
+    lib.shotkv_decode_workspace_bytes.restype = sz
+    lib.shotkv_decode_workspace_bytes.argtypes = [cfgp, i32, i32, i32]
+    lib.shotkv_decode_step.restype = ctypes.c_int
+    lib.shotkv_decode_step.argtypes = [cfgp, i32, ctypes.POINTER(_DecodeState), i32, vp, vp, vp, vp, vp,
+                                       vp, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ShotKVError(f"{what}: {load_library().shotkv_strerror(rc).decode()} ({rc})")
+
+
+def _dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.bfloat16:
+        return BF16
+    if dt == torch.float32:
+        return F32
+    raise ShotKVError(f"unsupported dtype {dt}")
+
+
+def _ptr(t, dtype=None, shape=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ShotKVError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ShotKVError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ShotKVError(f"{name} must be {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ShotKVError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _config(H, H_kv, D, W, dtype, sm_scale, select_mode):
+    return _Config(H, H_kv, D, W, _dtype_code(dtype), float(sm_scale), int(select_mode))
+
+
+def prefill_workspace_bytes(H, H_kv, D, W, dtype, P, n_tokens, n_shots, sm_scale=1.0,
+                            select_mode=SELECT_PREFIX) -> int:
+    cfg = _config(H, H_kv, D, W, dtype, sm_scale, select_mode)
+    n = load_library().shotkv_prefill_workspace_bytes(ctypes.byref(cfg), P, n_tokens, n_shots)
+    if n == 0:
+        raise ShotKVError("unsupported prefill shape")
+    return int(n)
+
+
+@dataclasses.dataclass
+class PrefillResult:
+    k_out: torch.Tensor           # [P, H_kv, cap, D]
+    v_out: torch.Tensor
+    kept_positions: torch.Tensor  # [P, cap] int32
+    kept_count: torch.Tensor      # [P] int32
+    shot_scores: torch.Tensor     # [P, n] float32
+    shot_selected: torch.Tensor   # [P, n] uint8
+    status: torch.Tensor          # [P] int32
+
+
+def _alloc_prefill_outputs(k, P, H_kv, cap, D, n, with_scores=True):
+    dev = k.device
+    return PrefillResult(
+        k_out=torch.empty((P, H_kv, cap, D), dtype=k.dtype, device=dev),
+        v_out=torch.empty((P, H_kv, cap, D), dtype=k.dtype, device=dev),
+        kept_positions=torch.empty((P, cap), dtype=torch.int32, device=dev),
+        kept_count=torch.empty((P,), dtype=torch.int32, device=dev),
+        shot_scores=torch.empty((P, n), dtype=torch.float32, device=dev) if with_scores else None,
+        shot_selected=torch.empty((P, n), dtype=torch.uint8, device=dev),
+        status=torch.empty((P,), dtype=torch.int32, device=dev),
+    )
+
+
+def prefill_compress(q_obs, k, v, shot_offsets, budget_tokens, cap, sm_scale,
+                     select_mode=SELECT_PREFIX, out: PrefillResult | None = None, workspace=None):
+    """shotkv_prefill_compress.  q_obs [P,H,W,D], k/v [P,H_kv,N,D], shot_offsets [P,n+1] int32,
+    budget_tokens [P] int32 (all on the GPU).  Returns a PrefillResult; nothing is synchronised."""
+    P, H, W, D = q_obs.shape
+    _, H_kv, N, _ = k.shape
+    n = shot_offsets.shape[1] - 1
+    cfg = _config(H, H_kv, D, W, k.dtype, sm_scale, select_mode)
+    lib = load_library()
+    if out is None:
+        out = _alloc_prefill_outputs(k, P, H_kv, cap, D, n)
+    if workspace is None:
+        workspace = torch.empty(prefill_workspace_bytes(H, H_kv, D, W, k.dtype, P, N, n, sm_scale),
+                                dtype=torch.uint8, device=k.device)
+    rc = lib.shotkv_prefill_compress(
+        ctypes.byref(cfg), P, N, n,
+        _ptr(q_obs, k.dtype, (P, H, W, D), "q_obs"), _ptr(k, None, (P, H_kv, N, D), "k"),
+        _ptr(v, k.dtype, (P, H_kv, N, D), "v"),
+        _ptr(shot_offsets, torch.int32, (P, n + 1), "shot_offsets"),
+        _ptr(budget_tokens, torch.int32, (P,), "budget_tokens"),
+        _ptr(out.k_out, k.dtype, (P, H_kv, cap, D), "k_out"),
+        _ptr(out.v_out, k.dtype, (P, H_kv, cap, D), "v_out"), cap,
+        _ptr(out.kept_positions, torch.int32, (P, cap), "kept_positions"),
+        _ptr(out.kept_count, torch.int32, (P,), "kept_count"),
+        _ptr(out.shot_scores, torch.float32, (P, n), "shot_scores"),
+        _ptr(out.shot_selected, torch.uint8, (P, n), "shot_selected"),
+        _ptr(out.status, torch.int32, (P,), "status"),
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
+    _check(rc, "shotkv_prefill_compress")
+    return out
+
+
+def prefill_scores(q_obs, k, shot_offsets, sm_scale, workspace=None):
+    """shotkv_prefill_scores.  Returns (shot_scores [P,n] float32, status [P] int32)."""
+    P, H, W, D = q_obs.shape
+    _, H_kv, N, _ = k.shape
+    n = shot_offsets.shape[1] - 1
+    cfg = _config(H, H_kv, D, W, k.dtype, sm_scale, SELECT_PREFIX)
+    lib = load_library()
+    scores = torch.empty((P, n), dtype=torch.float32, device=k.device)
+    status = torch.empty((P,), dtype=torch.int32, device=k.device)
+    if workspace is None:
+        workspace = torch.empty(prefill_workspace_bytes(H, H_kv, D, W, k.dtype, P, N, n, sm_scale),
+                                dtype=torch.uint8, device=k.device)
+    rc = lib.shotkv_prefill_scores(
+        ctypes.byref(cfg), P, N, n, _ptr(q_obs, k.dtype, (P, H, W, D), "q_obs"),
+        _ptr(k, None, (P, H_kv, N, D), "k"), _ptr(shot_offsets, torch.int32, (P, n + 1), "shot_offsets"),
+        _ptr(scores), _ptr(status), _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(),
+        _stream())
+    _check(rc, "shotkv_prefill_scores")
+    return scores, status
+
+
+def select_and_compact(shot_scores, k, v, shot_offsets, budget_tokens, cap, H, W,
+                       select_mode=SELECT_PREFIX, workspace=None):
+    """shotkv_select_and_compact from caller-supplied scores [P,n] float32.  Returns a PrefillResult
+    whose shot_scores is the input tensor."""
+    P, H_kv, N, D = k.shape
+    n = shot_offsets.shape[1] - 1
+    cfg = _config(H, H_kv, D, W, k.dtype, 1.0, select_mode)
+    lib = load_library()
+    out = _alloc_prefill_outputs(k, P, H_kv, cap, D, n, with_scores=False)
+    out.shot_scores = shot_scores
+    if workspace is None:
+        workspace = torch.empty(prefill_workspace_bytes(H, H_kv, D, W, k.dtype, P, N, n),
+                                dtype=torch.uint8, device=k.device)
+    rc = lib.shotkv_select_and_compact(
+        ctypes.byref(cfg), P, N, n, _ptr(shot_scores, torch.float32, (P, n), "shot_scores"),
+        _ptr(k, None, (P, H_kv, N, D), "k"), _ptr(v, k.dtype, (P, H_kv, N, D), "v"),
+        _ptr(shot_offsets, torch.int32, (P, n + 1), "shot_offsets"),
+        _ptr(budget_tokens, torch.int32, (P,), "budget_tokens"), _ptr(out.k_out), _ptr(out.v_out), cap,
+        _ptr(out.kept_positions), _ptr(out.kept_count), _ptr(out.shot_selected), _ptr(out.status),
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
+    _check(rc, "shotkv_select_and_compact")
+    return out
+
+
+class DecodeState:
+    """Caller-owned decode buffers of one layer (see shotkv_decode_state in include/shotkv.h)."""
+
+    def __init__(self, k_prefill, v_prefill, prefill_count, k_dec, v_dec, slot_pos, decode_budget,
+                 n_q_heads, sm_scale):
+        S, H_kv, cap, D = k_prefill.shape
+        n_slots = k_dec.shape[2]
+        self.S, self.H_kv, self.cap, self.D, self.n_slots = S, H_kv, cap, D, n_slots
+        self.H = n_q_heads
+        self.dtype = k_prefill.dtype
+        self.sm_scale = float(sm_scale)
+        self.decode_budget = int(decode_budget)
+        self.k_prefill, self.v_prefill, self.prefill_count = k_prefill, v_prefill, prefill_count
+        self.k_dec, self.v_dec, self.slot_pos = k_dec, v_dec, slot_pos
+        self.cfg = _config(self.H, H_kv, D, 1, self.dtype, sm_scale, SELECT_PREFIX)
+        self.c_state = _DecodeState(
+            _ptr(k_prefill, self.dtype, None, "k_prefill"), _ptr(v_prefill, self.dtype, (S, H_kv, cap, D), "v_prefill"),
+            _ptr(prefill_count, torch.int32, (S,), "prefill_count"),
+            _ptr(k_dec, self.dtype, (S, H_kv, n_slots, D), "k_dec"),
+            _ptr(v_dec, self.dtype, (S, H_kv, n_slots, D), "v_dec"),
+            _ptr(slot_pos, torch.int32, (S, n_slots), "slot_pos"), cap, n_slots, self.decode_budget)
+        nbytes = load_library().shotkv_decode_workspace_bytes(ctypes.byref(self.cfg), S, cap, n_slots)
+        if nbytes == 0:
+            raise ShotKVError("unsupported decode shape")
+        dev = k_prefill.device
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        self.out = torch.empty((S, self.H, D), dtype=torch.float32, device=dev)
+        self.token_scores = torch.empty((S, n_slots), dtype=torch.float32, device=dev)
+        self.evicted_pos = torch.empty((S,), dtype=torch.int32, device=dev)
+        self.status = torch.empty((S,), dtype=torch.int32, device=dev)
+
+
+def decode_step(state: DecodeState, step_index: int, q_new, k_new, v_new, want_scores=True):
+    """shotkv_decode_step on `state` (updated in place).  q_new [S,H,D], k_new/v_new [S,H_kv,D].
+    Results land in state.out / token_scores / evicted_pos / status; nothing is synchronised."""
+    S, H, H_kv, D = state.S, state.H, state.H_kv, state.D
+    rc = load_library().shotkv_decode_step(
+        ctypes.byref(state.cfg), S, ctypes.byref(state.c_state), int(step_index),
+        _ptr(q_new, state.dtype, (S, H, D), "q_new"), _ptr(k_new, state.dtype, (S, H_kv, D), "k_new"),
+        _ptr(v_new, state.dtype, (S, H_kv, D), "v_new"), _ptr(state.out),
+        _ptr(state.token_scores) if want_scores else None, _ptr(state.evicted_pos), _ptr(state.status),
+        _ptr(state.workspace), state.workspace.numel(), _stream())
+    _check(rc, "shotkv_decode_step")
+    return state.out

@@ -162,20 +162,28 @@ def prefill_batch(shape: PrefillShape, device="cpu", seed: int = 0, n_problems: 
     return q, k, v, torch.from_numpy(offs).to(device), torch.from_numpy(budgets).to(device)
 
 
-def decode_state(shape: DecodeShape, device="cpu", seed: int = 0, n_slots: int | None = None):
-    """Fresh decode state for every sequence: a random-normal compressed prefill cache with
-    prefill_count live rows and an empty slot pool of decode_budget + 1 slots."""
+def decode_state(shape: DecodeShape, device="cpu", seed: int = 0, n_slots: int | None = None,
+                 resident: int = 0):
+    """Decode state for every sequence: a random-normal compressed prefill cache with prefill_count live
+    rows and a slot pool of decode_budget + 1 slots.  `resident` generated tokens (indices 0..resident-1,
+    random-normal K/V) already sit in the first slots, as if that many steps had run without eviction."""
     S, Hkv, D = shape.n_seqs, shape.n_kv_heads, shape.head_dim
     n_slots = shape.decode_budget + 1 if n_slots is None else n_slots
+    assert 0 <= resident <= min(n_slots, shape.decode_budget)
     cap = shape.prefill_count
     kp = _randn((S, Hkv, cap, D), shape.dtype, device, _seed(seed, 10))
     vp = _randn((S, Hkv, cap, D), shape.dtype, device, _seed(seed, 11))
+    k_dec = torch.zeros((S, Hkv, n_slots, D), dtype=shape.dtype, device=device)
+    v_dec = torch.zeros((S, Hkv, n_slots, D), dtype=shape.dtype, device=device)
+    slot_pos = torch.full((S, n_slots), -1, dtype=torch.int32, device=device)
+    if resident > 0:
+        k_dec[:, :, :resident] = _randn((S, Hkv, resident, D), shape.dtype, device, _seed(seed, 12))
+        v_dec[:, :, :resident] = _randn((S, Hkv, resident, D), shape.dtype, device, _seed(seed, 13))
+        slot_pos[:, :resident] = torch.arange(resident, dtype=torch.int32, device=device)
     return {
         "k_prefill": kp, "v_prefill": vp,
         "prefill_count": torch.full((S,), cap, dtype=torch.int32, device=device),
-        "k_dec": torch.zeros((S, Hkv, n_slots, D), dtype=shape.dtype, device=device),
-        "v_dec": torch.zeros((S, Hkv, n_slots, D), dtype=shape.dtype, device=device),
-        "slot_pos": torch.full((S, n_slots), -1, dtype=torch.int32, device=device),
+        "k_dec": k_dec, "v_dec": v_dec, "slot_pos": slot_pos,
         "n_slots": n_slots, "cap": cap, "decode_budget": shape.decode_budget,
     }
 

@@ -1,0 +1,55 @@
+"""The C-ABI library loads without a GPU and exports every symbol the public header declares."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2502_01941_amd import build, shotkv
+    if not os.path.exists(shotkv.LIB_PATH):
+        build.build(force=True)
+    return shotkv.load_library()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "shotkv.h")).read()
+    return re.findall(r"SHOTKV_API\s+[\w\s\*]+?\b(shotkv_\w+)\s*\(", text)
+
+
+def test_header_symbols_are_exported(lib):
+    from paper_2502_01941_amd import shotkv
+    names = _declared_symbols()
+    assert len(names) >= 8 and set(names) == set(shotkv.EXPORTS)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_host_only_entry_points(lib):
+    from paper_2502_01941_amd import shotkv
+    assert lib.shotkv_abi_version() == 1
+    assert lib.shotkv_strerror(0) == b"ok"
+    assert b"workspace" in lib.shotkv_strerror(-3)
+    n = shotkv.prefill_workspace_bytes(32, 8, 128, 32, torch.bfloat16, 4, 32768, 160)
+    assert 0 < n < (1 << 30)
+    assert shotkv.prefill_workspace_bytes(32, 8, 128, 32, torch.bfloat16, 8, 32768, 160) > n
+    cfg = shotkv._config(32, 8, 96, 32, torch.bfloat16, 0.1, 0)          # head_dim 96 is unsupported
+    assert lib.shotkv_prefill_workspace_bytes(ctypes.byref(cfg), 1, 1000, 4) == 0
+    cfg = shotkv._config(32, 8, 128, 32, torch.bfloat16, 0.1, 0)
+    assert lib.shotkv_prefill_workspace_bytes(ctypes.byref(cfg), 1, 1000, 5000) == 0   # too many shots
+    assert lib.shotkv_decode_workspace_bytes(ctypes.byref(cfg), 16, 4096, 1025) > 0
+
+
+def test_null_arguments_are_rejected_before_any_launch(lib):
+    from paper_2502_01941_amd import shotkv
+    cfg = shotkv._config(32, 8, 128, 32, torch.bfloat16, 0.1, 0)
+    rc = lib.shotkv_prefill_scores(ctypes.byref(cfg), 1, 1000, 4, None, None, None, None, None, None, 0, None)
+    assert rc == -1
+    rc = lib.shotkv_decode_step(ctypes.byref(cfg), 1, None, 0, None, None, None, None, None, None, None,
+                                None, 0, None)
+    assert rc == -1

@@ -1,0 +1,154 @@
+"""GPU parity: decode steps through the C ABI against the CPU oracle, in lock step on the same inputs."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import to_np
+from oracle import shotkv_oracle as orc
+from paper_2502_01941_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+OUT_TOL = 1e-3        # |dO| <= OUT_TOL * max|O| per head row (fp32 accumulation on the device)
+SCORE_RTOL = 1e-3
+MARGIN_EXACT = 1e-6   # eviction must agree when the two lowest candidate scores differ by more
+
+
+@pytest.fixture(scope="module")
+def kv():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2502_01941_amd import shotkv
+    shotkv.load_library()
+    return shotkv
+
+
+class OracleSeq:
+    """Host-side state of one sequence, advanced only by the oracle's own decisions."""
+
+    def __init__(self, st, s):
+        self.kp = to_np(st["k_prefill"][s]).astype(np.float64)
+        self.vp = to_np(st["v_prefill"][s]).astype(np.float64)
+        self.pc = int(st["prefill_count"][s].item())
+        self.kd = to_np(st["k_dec"][s]).copy(); self.vd = to_np(st["v_dec"][s]).copy()
+        self.slot_pos = st["slot_pos"][s].cpu().numpy().copy()
+
+    def step(self, budget, step, q, kn, vn, scale):
+        return orc.decode_step(self.kp, self.vp, self.pc, self.kd, self.vd, self.slot_pos, budget, step,
+                               to_np(q), to_np(kn), to_np(vn), scale)
+
+
+def _make_state(kv, shape, st):
+    return kv.DecodeState(st["k_prefill"], st["v_prefill"], st["prefill_count"], st["k_dec"], st["v_dec"],
+                          st["slot_pos"], st["decode_budget"], shape.n_q_heads, shape.sm_scale)
+
+
+def _compare_step(state, s, r, seq, near_ties):
+    """Device results of sequence s against the oracle's step result r."""
+    assert int(state.status[s].item()) == r["status"]
+    out = state.out[s].cpu().numpy().astype(np.float64)
+    scale = np.abs(r["out"]).max(axis=1, keepdims=True)
+    assert np.all(np.abs(out - r["out"]) <= OUT_TOL * scale), np.abs(out - r["out"]).max()
+    ts = state.token_scores[s].cpu().numpy()
+    np.testing.assert_allclose(ts, r["token_scores"], rtol=SCORE_RTOL, atol=1e-30)
+    ev = int(state.evicted_pos[s].item())
+    if ev != r["evicted_pos"]:
+        # only legitimate when the two lowest scores are closer than the arithmetic can resolve: then
+        # the device must have taken the other one of the pair; follow it so the states stay aligned
+        assert r["margin"] < MARGIN_EXACT, (ev, r["evicted_pos"], r["margin"])
+        alt_slot = int(np.flatnonzero(seq.slot_pos == ev)[0])
+        cand = sorted((r["token_scores"][i], i) for i in np.flatnonzero(seq.slot_pos >= 0) if i != r["new_slot"])
+        assert alt_slot == cand[0][1]          # after the oracle's eviction the runner-up is now the lowest
+        seq.slot_pos[r["evicted_slot"]] = r["evicted_pos"]
+        seq.slot_pos[alt_slot] = -1
+        near_ties.append((s, ev))
+    np.testing.assert_array_equal(state.slot_pos[s].cpu().numpy(), seq.slot_pos)
+
+
+def test_tiny_free_running_320_steps(kv):
+    """S=1, H=4, D=64, fp32, budget 32: every step's output, token scores, eviction and slot map."""
+    shape = wl.DECODE_TINY
+    st = wl.decode_state(shape, "cuda")
+    state = _make_state(kv, shape, st)
+    seq = OracleSeq(st, 0)
+    kp_before = st["k_prefill"].clone()
+    near = []
+    for step in range(shape.n_steps):
+        q, kn, vn = wl.decode_inputs(shape, step, "cuda")
+        kv.decode_step(state, step, q, kn, vn)
+        torch.cuda.synchronize()
+        r = seq.step(shape.decode_budget, step, q[0], kn[0], vn[0], shape.sm_scale)
+        _compare_step(state, 0, r, seq, near)
+        occupied = int((state.slot_pos[0] >= 0).sum().item())
+        assert occupied == min(step + 1, shape.decode_budget)
+    assert len(near) == 0, near
+    assert torch.equal(st["k_prefill"], kp_before)            # the prefill cache stays fixed
+    np.testing.assert_array_equal(to_np(st["k_dec"][0]), seq.kd)
+    np.testing.assert_array_equal(to_np(st["v_dec"][0]), seq.vd)
+
+
+def test_decode4k_bf16_lockstep(kv):
+    """The long-generation shape (16 sequences, 4096-token prefill cache, budget 1024) around the point
+    where eviction starts: the state holds 1000 generated tokens, 64 more steps follow; two sequences
+    are followed by the oracle at every step."""
+    shape = wl.DECODE4K
+    resident = 1000
+    st = wl.decode_state(shape, "cuda", resident=resident)
+    state = _make_state(kv, shape, st)
+    tracked = {0: OracleSeq(st, 0), 11: OracleSeq(st, 11)}
+    vsum_before = st["v_prefill"].float().sum().item()
+    near = []
+    for step in range(resident, resident + 64):
+        q, kn, vn = wl.decode_inputs(shape, step, "cuda")
+        kv.decode_step(state, step, q, kn, vn)
+        torch.cuda.synchronize()
+        for s, seq in tracked.items():
+            r = seq.step(shape.decode_budget, step, q[s], kn[s], vn[s], shape.sm_scale)
+            _compare_step(state, s, r, seq, near)
+            assert (r["evicted_pos"] >= 0) == (step >= shape.decode_budget)
+        assert state.status.cpu().tolist() == [0] * shape.n_seqs
+    counts = (state.slot_pos >= 0).sum(dim=1).cpu().tolist()
+    assert counts == [shape.decode_budget] * shape.n_seqs
+    assert st["v_prefill"].float().sum().item() == vsum_before
+    assert len(near) <= 2, near
+
+
+def test_partial_prefill_and_unbounded_budget(kv):
+    """prefill_count below cap (rows past it must be ignored), G=2, and the prefill-only ablation:
+    with an unbounded budget nothing is ever evicted; a full pool reports its own status."""
+    shape = wl.DecodeShape("odd", 3, 8, 4, 128, 100, kv.INT32_MAX, 0, torch.bfloat16)
+    st = wl.decode_state(shape, "cuda", n_slots=6)
+    st["prefill_count"] = torch.tensor([100, 37, 0], dtype=torch.int32, device="cuda")
+    state = _make_state(kv, shape, st)
+    seqs = [OracleSeq(st, s) for s in range(3)]
+    near = []
+    for step in range(7):
+        q, kn, vn = wl.decode_inputs(shape, step, "cuda")
+        kv.decode_step(state, step, q, kn, vn)
+        torch.cuda.synchronize()
+        for s in range(3):
+            r = seqs[s].step(kv.INT32_MAX, step, q[s], kn[s], vn[s], shape.sm_scale)
+            if step < 6:
+                _compare_step(state, s, r, seqs[s], near)
+                assert r["evicted_pos"] == -1
+            else:
+                assert r["status"] == orc.STATUS_NO_FREE_SLOT
+                assert int(state.status[s].item()) == orc.STATUS_NO_FREE_SLOT
+                np.testing.assert_array_equal(state.slot_pos[s].cpu().numpy(), seqs[s].slot_pos)
+
+
+def test_equal_scores_evict_newest_previous_token(kv):
+    """All decode keys identical -> equal token scores; the evicted token must be the newest earlier
+    one, never the token just appended."""
+    shape = wl.DecodeShape("ties", 1, 4, 4, 64, 8, 3, 0, torch.float32)
+    st = wl.decode_state(shape, "cuda")
+    state = _make_state(kv, shape, st)
+    q = torch.ones((1, 4, 64), device="cuda")
+    kn = torch.full((1, 4, 64), 0.25, device="cuda")
+    vn = torch.ones((1, 4, 64), device="cuda")
+    evicted = []
+    for step in range(6):
+        kv.decode_step(state, step, q, kn, vn)
+        torch.cuda.synchronize()
+        evicted.append(int(state.evicted_pos[0].item()))
+    assert evicted == [-1, -1, -1, 2, 3, 4]

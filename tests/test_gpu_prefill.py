@@ -1,0 +1,240 @@
+"""GPU parity: prefill compression through the C ABI against the CPU oracle on the same seeded inputs."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import helpers
+from helpers import check_prefill_problem, oracle_prefill, to_np
+from oracle import shotkv_oracle as orc
+from paper_2502_01941_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kv():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2502_01941_amd import shotkv
+    shotkv.load_library()
+    return shotkv
+
+
+def _run_shape(kv, shape, n_problems=None, mode=orc.SELECT_PREFIX, seed=0):
+    q, k, v, off, bud = wl.prefill_batch(shape, "cuda", seed=seed, n_problems=n_problems)
+    res = kv.prefill_compress(q, k, v, off, bud, shape.budget_tokens, shape.sm_scale, mode)
+    torch.cuda.synchronize()
+    return q, k, v, off, bud, res
+
+
+def test_tiny_fp32_full_parity(kv):
+    """fp32, D=64, G=1, W=16, 8 shots: every output against the oracle."""
+    shape = wl.TINY
+    q, k, v, off, bud, res = _run_shape(kv, shape)
+    ref = check_prefill_problem(res, 0, q[0], k[0], v[0], off[0].cpu().numpy(), shape.budget_tokens,
+                                shape.budget_tokens, shape.sm_scale)
+    assert ref["margin"] >= helpers.MARGIN_EXACT
+    # tighter than the stated bound: fp32 inputs, 512 keys
+    np.testing.assert_allclose(res.shot_scores[0].cpu().numpy(), ref["scores"], rtol=2e-5)
+
+
+def test_layer8k_bf16_full_parity(kv):
+    """One Llama-3-8B-shaped layer, 8192 tokens, 40 shots, budget 40 %."""
+    shape = wl.LAYER8K
+    q, k, v, off, bud, res = _run_shape(kv, shape)
+    report = []
+    ref = check_prefill_problem(res, 0, q[0], k[0], v[0], off[0].cpu().numpy(), shape.budget_tokens,
+                                shape.budget_tokens, shape.sm_scale, report=report)
+    assert not report, report
+    # mass conservation on the device's own scores: sum k_i*Score_i <= H*W, the rest sits in the tail
+    lengths = np.diff(off[0].cpu().numpy())
+    gpu_mass = float((lengths * res.shot_scores[0].cpu().numpy().astype(np.float64)).sum())
+    tail_mass = float(ref["mass"][off[0, -1].item():].sum())
+    assert abs(gpu_mass + tail_mass - 32 * 32) < 1e-2
+
+
+def _ragged_problem(P, H, Hkv, D, W, N, dtype, seed, n_shots, prefix, tail_min):
+    """Uneven shots with a non-empty prefix, sizes that are not multiples of any tile."""
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    q = torch.randn((P, H, W, D), generator=g, device="cuda").to(dtype)
+    k = torch.randn((P, Hkv, N, D), generator=g, device="cuda").to(dtype)
+    v = torch.randn((P, Hkv, N, D), generator=g, device="cuda").to(dtype)
+    rng = np.random.default_rng(seed)
+    offs = np.zeros((P, n_shots + 1), dtype=np.int32)
+    for p in range(P):
+        cuts = np.sort(rng.choice(np.arange(prefix + 1, N - tail_min), size=n_shots, replace=False))
+        offs[p] = np.concatenate([[prefix], cuts])
+    return q, k, v, torch.from_numpy(offs).cuda()
+
+
+@pytest.mark.parametrize("H,Hkv,D,W,N,dtype,n_shots", [
+    (32, 8, 128, 32, 2999, torch.bfloat16, 17),   # the Llama shape, ragged everything
+    (8, 2, 128, 32, 1537, torch.bfloat16, 9),     # G=4, fewer heads
+    (16, 8, 128, 32, 700, torch.bfloat16, 5),     # G=2 -> 64 rows per KV head
+    (8, 8, 128, 32, 650, torch.bfloat16, 4),      # G=1 -> 32 rows
+    (16, 4, 128, 16, 900, torch.bfloat16, 6),     # W=16, G=4 -> 64 rows
+    (8, 4, 64, 16, 777, torch.float32, 6),        # fp32, D=64
+    (4, 4, 128, 8, 300, torch.float32, 3),        # fp32, D=128
+    (8, 2, 64, 24, 500, torch.bfloat16, 5),       # bf16, D=64, W not a power of two
+])
+def test_ragged_shapes(kv, H, Hkv, D, W, N, dtype, n_shots):
+    P = 3
+    q, k, v, off = _ragged_problem(P, H, Hkv, D, W, N, dtype, 1234 + N, n_shots, prefix=7, tail_min=W + 3)
+    budgets = torch.tensor([N // 2, N // 3, N], dtype=torch.int32, device="cuda")
+    cap = N
+    scale = 1.0 / math.sqrt(D)
+    res = kv.prefill_compress(q, k, v, off, budgets, cap, scale)
+    torch.cuda.synchronize()
+    for p in range(P):
+        check_prefill_problem(res, p, q[p], k[p], v[p], off[p].cpu().numpy(), budgets[p].item(), cap, scale)
+
+
+def test_shot_reaching_into_the_window(kv):
+    """The last shot may contain window positions: its keys are then causally masked per query row."""
+    H, Hkv, D, W, N = 8, 2, 128, 32, 600
+    q, k, v, _ = _ragged_problem(1, H, Hkv, D, W, N, torch.bfloat16, 5, 3, 0, 40)
+    off = torch.tensor([[0, 200, 410, 590]], dtype=torch.int32, device="cuda")   # window = [568, 600)
+    bud = torch.tensor([N], dtype=torch.int32, device="cuda")
+    res = kv.prefill_compress(q, k, v, off, bud, N, 0.1)
+    torch.cuda.synchronize()
+    check_prefill_problem(res, 0, q[0], k[0], v[0], off[0].cpu().numpy(), N, N, 0.1)
+
+
+def test_degenerate_problems_in_one_batch(kv):
+    """Bad offsets, a budget smaller than the always-kept tokens, an exact fit and a zero shot budget,
+    side by side with a healthy problem: each gets its own status and the others are unaffected."""
+    H, Hkv, D, W, N, n = 8, 2, 128, 32, 1000, 4
+    q, k, v, _ = _ragged_problem(5, H, Hkv, D, W, N, torch.bfloat16, 77, n, 0, 40)
+    off = np.array([[10, 200, 400, 600, 900],
+                    [10, 200, 200, 600, 900],     # not strictly increasing
+                    [10, 200, 400, 600, 900],
+                    [10, 200, 400, 600, 900],
+                    [10, 200, 400, 600, 1001]],   # beyond n_tokens
+                   dtype=np.int32)
+    budgets = np.array([500, 500, 109, 110, 500], dtype=np.int32)   # always-kept = 10 + 100 = 110
+    res = kv.prefill_compress(q, k, v, torch.from_numpy(off).cuda(), torch.from_numpy(budgets).cuda(), 600, 0.09)
+    torch.cuda.synchronize()
+    assert res.status.cpu().tolist() == [orc.STATUS_OK, orc.STATUS_BAD_OFFSETS, orc.STATUS_BUDGET_TOO_SMALL,
+                                         orc.STATUS_OK, orc.STATUS_BAD_OFFSETS]
+    for p in range(5):
+        check_prefill_problem(res, p, q[p], k[p], v[p], off[p], budgets[p], 600, 0.09)
+    assert res.kept_count.cpu().tolist()[3] == 110
+
+
+def test_no_shots_keeps_everything(kv):
+    H, Hkv, D, W, N = 4, 4, 64, 16, 200
+    q, k, v, _ = _ragged_problem(2, H, Hkv, D, W, N, torch.float32, 3, 1, 0, 40)
+    off = torch.tensor([[50], [0]], dtype=torch.int32, device="cuda")
+    bud = torch.tensor([200, 199], dtype=torch.int32, device="cuda")
+    res = kv.prefill_compress(q, k, v, off, bud, 256, 0.125)
+    torch.cuda.synchronize()
+    assert res.status.cpu().tolist() == [orc.STATUS_OK, orc.STATUS_BUDGET_TOO_SMALL]
+    assert res.kept_count.cpu().tolist() == [200, 0]
+    assert res.kept_positions[0, :200].cpu().tolist() == list(range(200))
+    np.testing.assert_array_equal(helpers.bits(res.k_out[0, :, :200]), helpers.bits(k[0]))
+
+
+def test_uniform_keys_tie_break(kv):
+    """All keys identical: all shot scores are (nearly) equal, and with truly equal scores fed to the
+    selection half the lowest indices must win."""
+    H, Hkv, D, W, N, n = 8, 2, 128, 32, 1200, 10
+    g = torch.Generator(device="cuda").manual_seed(11)
+    q = torch.randn((1, H, W, D), generator=g, device="cuda").to(torch.bfloat16)
+    k = torch.randn((1, 1, 1, D), generator=g, device="cuda").to(torch.bfloat16).expand(1, Hkv, N, D).contiguous()
+    v = torch.randn((1, Hkv, N, D), generator=g, device="cuda").to(torch.bfloat16)
+    off = torch.arange(0, 1001, 100, dtype=torch.int32, device="cuda")[None]
+    bud = torch.tensor([200 + 350], dtype=torch.int32, device="cuda")
+    scores, status = kv.prefill_scores(q, k, off, 0.2)
+    torch.cuda.synchronize()
+    expect = H * sum(1.0 / (N - W + j + 1) for j in range(W))   # closed form for uniform attention
+    np.testing.assert_allclose(scores[0].cpu().numpy(), expect, rtol=1e-5)
+    equal = torch.full((1, n), float(expect), dtype=torch.float32, device="cuda")
+    res = kv.select_and_compact(equal, k, v, off, bud, 600, H, W)
+    torch.cuda.synchronize()
+    assert res.shot_selected[0].cpu().tolist() == [1, 1, 1] + [0] * 7
+
+
+@pytest.mark.parametrize("mode", [orc.SELECT_PREFIX, orc.SELECT_FIRST_FIT])
+def test_select_and_compact_synthetic_scores(kv, mode):
+    """The selection/compaction half on generator-made scores (with ties, -inf free): bit-exact against
+    the oracle's selection on the same scores, for many problems at once."""
+    P, H, Hkv, D, W, N, n = 64, 8, 2, 128, 32, 3000, 37
+    rng = np.random.default_rng(2024 + mode)
+    _, k, v, off = _ragged_problem(P, H, Hkv, D, W, N, torch.bfloat16, 99, n, 5, 50)
+    scores = rng.standard_normal((P, n)).astype(np.float32)
+    scores[::3] = np.round(scores[::3] * 2) / 2                     # heavy ties
+    budgets = rng.integers(50, N, size=P).astype(np.int32)
+    cap = 2048                                                      # some budgets get clamped to cap
+    res = kv.select_and_compact(torch.from_numpy(scores).cuda(), k, v, off, torch.from_numpy(budgets).cuda(),
+                                cap, H, W, mode)
+    torch.cuda.synchronize()
+    offs = off.cpu().numpy()
+    for p in range(P):
+        b = min(int(budgets[p]), cap)
+        lengths = np.diff(offs[p])
+        n_always = int(offs[p, 0]) + N - int(offs[p, -1])
+        if b - n_always < 0:
+            assert res.status[p].item() == orc.STATUS_BUDGET_TOO_SMALL and res.kept_count[p].item() == 0
+            continue
+        keep = orc.select_shots(scores[p], lengths, b - n_always, mode)
+        assert res.status[p].item() == orc.STATUS_OK
+        assert res.shot_selected[p].cpu().numpy().tolist() == keep.tolist(), p
+        pos = orc.kept_positions_from_mask(keep, offs[p], N)
+        kept = res.kept_count[p].item()
+        assert kept == pos.size
+        np.testing.assert_array_equal(res.kept_positions[p, :kept].cpu().numpy(), pos)
+        idx = torch.from_numpy(pos).long().cuda()
+        np.testing.assert_array_equal(helpers.bits(res.k_out[p, :, :kept]), helpers.bits(k[p][:, idx]))
+        np.testing.assert_array_equal(helpers.bits(res.v_out[p, :, :kept]), helpers.bits(v[p][:, idx]))
+
+
+def test_many_shots_selection(kv):
+    """Sentence-sized units: thousands of short spans stress the sort, the scans and the copy plan."""
+    P, H, Hkv, D, W, N, n = 2, 8, 2, 128, 32, 40000, 3000
+    _, k, v, off = _ragged_problem(P, H, Hkv, D, W, N, torch.bfloat16, 31, n, 3, 100)
+    rng = np.random.default_rng(8)
+    scores = rng.standard_normal((P, n)).astype(np.float32)
+    budgets = np.array([N // 10, N // 2], dtype=np.int32)
+    res = kv.select_and_compact(torch.from_numpy(scores).cuda(), k, v, off, torch.from_numpy(budgets).cuda(),
+                                N // 2, H, W)
+    torch.cuda.synchronize()
+    offs = off.cpu().numpy()
+    for p in range(P):
+        n_always = int(offs[p, 0]) + N - int(offs[p, -1])
+        keep = orc.select_shots(scores[p], np.diff(offs[p]), int(budgets[p]) - n_always)
+        assert res.shot_selected[p].cpu().numpy().tolist() == keep.tolist()
+        pos = orc.kept_positions_from_mask(keep, offs[p], N)
+        kept = res.kept_count[p].item()
+        np.testing.assert_array_equal(res.kept_positions[p, :kept].cpu().numpy(), pos)
+        idx = torch.from_numpy(pos).long().cuda()
+        np.testing.assert_array_equal(helpers.bits(res.v_out[p, :, :kept]), helpers.bits(v[p][:, idx]))
+
+
+def test_inputs_are_not_modified_and_runs_repeat_bitwise(kv):
+    shape = wl.LAYER8K
+    q, k, v, off, bud = wl.prefill_batch(shape, "cuda")
+    k0, v0, q0 = k.clone(), v.clone(), q.clone()
+    a = kv.prefill_compress(q, k, v, off, bud, shape.budget_tokens, shape.sm_scale)
+    b = kv.prefill_compress(q, k, v, off, bud, shape.budget_tokens, shape.sm_scale)
+    torch.cuda.synchronize()
+    assert torch.equal(k, k0) and torch.equal(v, v0) and torch.equal(q, q0)
+    assert torch.equal(a.shot_scores, b.shot_scores)              # fixed summation order: no atomics
+    assert torch.equal(a.kept_positions[:, : a.kept_count[0]], b.kept_positions[:, : b.kept_count[0]])
+
+
+def test_host_side_errors(kv):
+    q = torch.zeros((1, 8, 32, 128), dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros((1, 2, 100, 128), dtype=torch.bfloat16, device="cuda")
+    off = torch.tensor([[0, 10]], dtype=torch.int32, device="cuda")
+    bud = torch.tensor([50], dtype=torch.int32, device="cuda")
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(kv.ShotKVError, match="workspace"):
+        kv.prefill_compress(q, k, k, off, bud, 64, 0.1, workspace=small)
+    with pytest.raises(kv.ShotKVError, match="shape"):                 # window longer than the prompt
+        kv.prefill_compress(q, k[:, :, :20].contiguous(), k[:, :, :20].contiguous(), off, bud, 64, 0.1)
+    with pytest.raises(kv.ShotKVError, match="aligned"):
+        ws = torch.empty(kv.prefill_workspace_bytes(8, 2, 128, 32, torch.bfloat16, 1, 100, 1) + 16,
+                         dtype=torch.uint8, device="cuda")
+        kv.prefill_compress(q, k, k, off, bud, 64, 0.1, workspace=ws[8:])
