@@ -1,0 +1,193 @@
+"""Benchmark of the ShotKV hot path on one MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic input: prefill compression (chunk
+plan, window-attention scores, per-shot reduction, selection, K/V compaction) of all 128 (layer, batch)
+problems of the 32-layer x batch-4 x 32K-token Llama-3-8B-shaped workload, followed by one decode step
+(attention over the compressed caches + token retention) for the same 128 (layer, sequence) caches.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload model32k|layer8k|skew128k]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+
+
+def _kv_bytes_per_token(shape):
+    esize = 2 if str(shape.dtype).endswith("bfloat16") else 4
+    return shape.n_kv_heads * shape.head_dim * esize
+
+
+def cpu_baseline(shape, n_problems, seed):
+    """The CPU oracle as it stands, timed on this host on the first problems of the same workload."""
+    import numpy as np
+    import torch
+    from oracle import shotkv_oracle as orc
+    from paper_2502_01941_amd import workloads as wl
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:  # pragma: no cover
+        threads = os.cpu_count() or 1
+    host = lambda t: (t.float() if t.dtype == torch.bfloat16 else t).numpy()
+    total = 0.0
+    done = 0
+    for p in range(n_problems):
+        q, k, v, off = wl.prefill_problem(shape, p, "cpu", seed)
+        qn, kn, vn = host(q), host(k), host(v)
+        t0 = time.perf_counter()
+        orc.prefill_compress(qn, kn, vn, off, shape.budget_tokens, shape.sm_scale)
+        total += time.perf_counter() - t0
+        done += 1
+        if total > 12.0:
+            break
+    return {
+        "value": done * shape.n_tokens / total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"prefill compression of the first {done} of {shape.n_problems} problems of {shape.name} "
+                  f"(numpy float64, {total:.1f} s); decode step not included",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="model32k")
+    ap.add_argument("--decode-steps", type=int, default=200)
+    ap.add_argument("--cpu-problems", type=int, default=128)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode-bench", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU's throughput; this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2502_01941_amd import shotkv, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    shotkv.load_library()
+    torch.cuda.set_device(0)
+    shape = wl.PREFILL_SHAPES[args.workload]
+    seed = 0
+    P, N = shape.n_problems, shape.n_tokens
+    cap = shape.budget_tokens
+
+    # ---- resident inputs and caller-owned buffers -------------------------------------------------
+    q, k, v, off, bud = wl.prefill_batch(shape, "cuda", seed)
+    n = shape.n_shots
+    ws = torch.empty(shotkv.prefill_workspace_bytes(shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                                                    shape.window, shape.dtype, P, N, n, shape.sm_scale),
+                     dtype=torch.uint8, device="cuda")
+    out = shotkv._alloc_prefill_outputs(k, P, shape.n_kv_heads, cap, shape.head_dim, n)
+    dec_budget, n_slots = 1024, 1025
+    k_dec = torch.zeros((P, shape.n_kv_heads, n_slots, shape.head_dim), dtype=shape.dtype, device="cuda")
+    v_dec = torch.zeros_like(k_dec)
+    slot_pos = torch.full((P, n_slots), -1, dtype=torch.int32, device="cuda")
+    dstate = shotkv.DecodeState(out.k_out, out.v_out, out.kept_count, k_dec, v_dec, slot_pos, dec_budget,
+                                shape.n_q_heads, shape.sm_scale)
+    dshape = wl.DecodeShape("bench", P, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, cap, dec_budget,
+                            0, shape.dtype)
+    qn, kn, vn = wl.decode_inputs(dshape, 0, "cuda", seed)
+
+    def step(i):
+        shotkv.prefill_compress(q, k, v, off, bud, cap, shape.sm_scale, out=out, workspace=ws)
+        shotkv.decode_step(dstate, i, qn, kn, vn, want_scores=False)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    shotkv.profile_enable(True)
+    shotkv.profile_read()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    stop.record()
+    torch.cuda.synchronize()
+    ms_per_step = start.elapsed_time(stop) / args.steps
+    prof = shotkv.profile_read()
+    shotkv.profile_enable(False)
+    assert int(out.status.abs().sum().item()) == 0 and int(dstate.status.abs().sum().item()) == 0
+
+    kernels = {name: {"avg_ms": ms / cnt, "launches": int(cnt)} for name, (ms, cnt) in prof.items() if cnt}
+    kept_total = int(out.kept_count.sum().item())
+    kvb = _kv_bytes_per_token(shape)
+    score_bytes = P * N * kvb                                   # K read once per launch
+    compact_bytes = 4 * kept_total * kvb                        # K and V, read + write
+    dec_tokens = kept_total + P * (args.warmup + args.steps)    # live rows read by the last decode step
+    kernels["score"]["algorithmic_gbps"] = score_bytes / kernels["score"]["avg_ms"] / 1e6
+    kernels["compact"]["algorithmic_gbps"] = compact_bytes / kernels["compact"]["avg_ms"] / 1e6
+    kernels["decode_partial"]["algorithmic_gbps"] = 2 * dec_tokens * kvb / kernels["decode_partial"]["avg_ms"] / 1e6
+    prefill_ms = sum(kernels[x]["avg_ms"] for x in ("plan", "score", "row_stats", "chunk_mass", "shot_scores",
+                                                    "select", "compact") if x in kernels)
+    algo_bytes_step = score_bytes + compact_bytes
+    achieved = kernels["score"]["algorithmic_gbps"]
+    result = {
+        "metric": "prefill-compress tokens/s per layer",
+        "value": P * N / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if kvb == shape.n_kv_heads * shape.head_dim * 2 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{shape.name}: {P} (layer,batch) problems x {N} tokens, {n} shots, "
+                               f"{shape.n_q_heads}q/{shape.n_kv_heads}kv heads, head_dim {shape.head_dim}, "
+                               f"window {shape.window}, budget {cap}; then 1 decode step over the "
+                               f"{P} compressed caches",
+                   "tokens_per_step": P * N, "kept_tokens": kept_total},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "kernel": "score_partials_mfma_kernel"},
+        "prefill": {"ms": prefill_ms, "tokens_per_s_per_layer": P * N / (prefill_ms * 1e-3),
+                    "algorithmic_gbps": algo_bytes_step / prefill_ms / 1e6,
+                    "hbm_frac": algo_bytes_step / prefill_ms / 1e6 / HBM_PEAK_GBPS},
+        "kernels": kernels,
+    }
+
+    # ---- decode step at the long-generation shape (16 sequences, 4096 + 1024 tokens) -------------
+    if not args.no_decode_bench:
+        del q, k, v, out, dstate, k_dec, v_dec, ws
+        torch.cuda.empty_cache()
+        d4 = wl.DECODE4K
+        st = wl.decode_state(d4, "cuda", seed, resident=d4.decode_budget)
+        state = shotkv.DecodeState(st["k_prefill"], st["v_prefill"], st["prefill_count"], st["k_dec"],
+                                   st["v_dec"], st["slot_pos"], d4.decode_budget, d4.n_q_heads, d4.sm_scale)
+        qs, ks, vs = wl.decode_inputs(d4, 0, "cuda", seed)
+        base = d4.decode_budget
+        for i in range(20):
+            shotkv.decode_step(state, base + i, qs, ks, vs)
+        torch.cuda.synchronize()
+        start.record()
+        for i in range(args.decode_steps):
+            shotkv.decode_step(state, base + 20 + i, qs, ks, vs)
+        stop.record()
+        torch.cuda.synchronize()
+        us = start.elapsed_time(stop) * 1e3 / args.decode_steps
+        dbytes = d4.n_seqs * (d4.prefill_count + d4.decode_budget + 1) * 2 * _kv_bytes_per_token(d4)
+        result["decode"] = {"workload": "decode4k: 16 sequences x (4096 prefill + 1024 decode) tokens, "
+                                        "eviction every step", "step_us": us,
+                            "algorithmic_gbps": dbytes / us / 1e3, "hbm_frac": dbytes / us / 1e3 / HBM_PEAK_GBPS,
+                            "steps": args.decode_steps}
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(shape, args.cpu_problems, seed)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -77,6 +77,18 @@ typedef struct {
 SHOTKV_API const char* shotkv_strerror(int code);
 SHOTKV_API int32_t shotkv_abi_version(void);
 
+/*
+ * Per-kernel timing for benchmarks (not part of the method).  While enabled, every kernel the library
+ * enqueues is bracketed by HIP events on the caller's stream.  shotkv_profile_read waits for the
+ * recorded launches, adds their durations per kernel kind into total_ms[kind] / launches[kind]
+ * (host arrays of n_kinds >= SHOTKV_KERNEL_KINDS entries) and forgets them.  Kinds, in order: chunk
+ * plan, score, row statistics, chunk mass, shot scores, selection, compaction, decode partial, decode
+ * finish.  Process-wide; the events are the only objects the library ever creates.
+ */
+#define SHOTKV_KERNEL_KINDS 9
+SHOTKV_API int shotkv_profile_enable(int enable);
+SHOTKV_API int shotkv_profile_read(double* total_ms, int64_t* launches, int32_t n_kinds);
+
 /* Bytes of device workspace shotkv_prefill_compress / _scores / _select_and_compact need for P
  * problems of n_tokens tokens and n_shots shots.  0 if the shape is unsupported. */
 SHOTKV_API size_t shotkv_prefill_workspace_bytes(const shotkv_config* cfg, int32_t P, int32_t n_tokens,

@@ -45,6 +45,26 @@ __host__ __device__ __forceinline__ int max_chunks(int n_tokens, int n_shots, in
   return ceil_div(n_tokens, chunk_keys) + n_shots + 2;
 }
 
+// ---- optional per-kernel timing (host) -----------------------------------------------------------
+
+enum KernelKind {
+  kKernelPlan = 0, kKernelScore, kKernelRowStats, kKernelChunkMass, kKernelShotScores, kKernelSelect,
+  kKernelCompact, kKernelDecodePartial, kKernelDecodeFinish, kKernelKinds
+};
+
+// Brackets one kernel launch with HIP events on its stream while profiling is enabled; free otherwise.
+class KernelTimer {
+ public:
+  KernelTimer(KernelKind kind, hipStream_t stream);
+  ~KernelTimer();
+  KernelTimer(const KernelTimer&) = delete;
+  KernelTimer& operator=(const KernelTimer&) = delete;
+
+ private:
+  hipEvent_t stop_ = nullptr;
+  hipStream_t stream_ = nullptr;
+};
+
 // ---- workspace carving (host) -------------------------------------------------------------------
 
 struct PrefillWorkspace {

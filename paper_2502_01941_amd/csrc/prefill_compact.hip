@@ -82,6 +82,7 @@ hipError_t launch_compact(const PrefillDims& d, const void* k, const void* v, vo
   const int row_bytes = d.D * (d.dtype == SHOTKV_BF16 ? 2 : 4);
   const dim3 grid(ceil_div(cap, kRowsPerBlock), d.H_kv, d.P * 2), block(kCopyThreads);
   const int max_runs = d.n_shots + 2;
+  KernelTimer timer(kKernelCompact, s);
 #define SHOTKV_LAUNCH_COMPACT(RB)                                                                      \
   hipLaunchKernelGGL(compact_kernel<RB>, grid, block, 0, s, static_cast<const char*>(k),               \
                      static_cast<const char*>(v), static_cast<char*>(k_out), static_cast<char*>(v_out), \

@@ -103,12 +103,19 @@ __global__ void shot_scores_kernel(const float* __restrict__ chunk_mass,
 hipError_t launch_reduce_scores(const PrefillDims& d, const int32_t* shot_offsets,
                                 const int32_t* status, float* shot_scores, const PrefillWorkspace& w,
                                 hipStream_t s) {
-  hipLaunchKernelGGL(row_stats_kernel, dim3(d.H_kv, d.P), dim3(kStatThreads), 0, s, w.partial,
-                     w.n_chunks, d.H_kv, d.R, w.max_c, w.row_stat);
-  hipLaunchKernelGGL(chunk_mass_kernel, dim3(ceil_div(w.max_c, kMassThreads / kWave), d.P),
-                     dim3(kMassThreads), 0, s, w.partial, w.row_stat, w.n_chunks, d.H_kv, d.R, w.max_c,
-                     w.chunk_mass);
+  {
+    KernelTimer timer(kKernelRowStats, s);
+    hipLaunchKernelGGL(row_stats_kernel, dim3(d.H_kv, d.P), dim3(kStatThreads), 0, s, w.partial,
+                       w.n_chunks, d.H_kv, d.R, w.max_c, w.row_stat);
+  }
+  {
+    KernelTimer timer(kKernelChunkMass, s);
+    hipLaunchKernelGGL(chunk_mass_kernel, dim3(ceil_div(w.max_c, kMassThreads / kWave), d.P),
+                       dim3(kMassThreads), 0, s, w.partial, w.row_stat, w.n_chunks, d.H_kv, d.R,
+                       w.max_c, w.chunk_mass);
+  }
   if (d.n_shots > 0) {
+    KernelTimer timer(kKernelShotScores, s);
     hipLaunchKernelGGL(shot_scores_kernel, dim3(ceil_div(d.n_shots, 256), d.P), dim3(256), 0, s,
                        w.chunk_mass, w.seg_first, shot_offsets, status, d.n_shots, w.max_c, shot_scores);
   }

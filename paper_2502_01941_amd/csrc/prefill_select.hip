@@ -177,6 +177,7 @@ hipError_t launch_select_plan(const PrefillDims& d, const float* shot_scores,
                               const int32_t* shot_offsets, const int32_t* budget_tokens, int cap,
                               int32_t* kept_count, uint8_t* shot_selected, int32_t* status,
                               const PrefillWorkspace& w, hipStream_t s) {
+  KernelTimer timer(kKernelSelect, s);
   hipLaunchKernelGGL(select_plan_kernel, dim3(d.P), dim3(kSelThreads), 0, s, shot_scores, shot_offsets,
                      budget_tokens, d.n_shots, d.n_tokens, d.W, cap, d.select_mode, kept_count,
                      shot_selected, status, w.n_runs, w.run_src, w.run_dst, w.run_len);

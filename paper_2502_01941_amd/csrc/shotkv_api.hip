@@ -2,7 +2,46 @@
 // Every entry point only enqueues work on the caller's stream.
 #include "common.hpp"
 
+#include <mutex>
+#include <vector>
+
 namespace shotkv {
+
+// ---- per-kernel timing ---------------------------------------------------------------------------
+
+namespace {
+struct TimedLaunch { int kind; hipEvent_t start, stop; };
+std::mutex g_prof_mutex;
+bool g_prof_enabled = false;
+std::vector<TimedLaunch> g_prof_launches;
+std::vector<hipEvent_t> g_prof_free_events;
+
+hipEvent_t take_event() {
+  if (!g_prof_free_events.empty()) {
+    hipEvent_t e = g_prof_free_events.back();
+    g_prof_free_events.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+}  // namespace
+
+KernelTimer::KernelTimer(KernelKind kind, hipStream_t stream) {
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  if (!g_prof_enabled) return;
+  hipEvent_t start = take_event(), stop = take_event();
+  if (!start || !stop) return;
+  (void)hipEventRecord(start, stream);
+  g_prof_launches.push_back({static_cast<int>(kind), start, stop});
+  stop_ = stop;
+  stream_ = stream;
+}
+
+KernelTimer::~KernelTimer() {
+  if (stop_) (void)hipEventRecord(stop_, stream_);
+}
 
 hipError_t launch_score_partials_generic(const PrefillDims& d, const void* q_obs, const void* k,
                                          const PrefillWorkspace& w, hipStream_t s);
@@ -75,6 +114,33 @@ const char* shotkv_strerror(int code) {
 }
 
 int32_t shotkv_abi_version(void) { return 1; }
+
+int shotkv_profile_enable(int enable) {
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  g_prof_enabled = enable != 0;
+  return SHOTKV_OK;
+}
+
+int shotkv_profile_read(double* total_ms, int64_t* launches, int32_t n_kinds) {
+  if (!total_ms || !launches) return SHOTKV_E_NULL;
+  if (n_kinds < kKernelKinds) return SHOTKV_E_SHAPE;
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  for (int i = 0; i < n_kinds; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
+  int rc = SHOTKV_OK;
+  for (const TimedLaunch& t : g_prof_launches) {
+    float ms = 0.f;
+    if (hipEventSynchronize(t.stop) == hipSuccess && hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) {
+      total_ms[t.kind] += ms;
+      launches[t.kind] += 1;
+    } else {
+      rc = SHOTKV_E_LAUNCH;
+    }
+    g_prof_free_events.push_back(t.start);
+    g_prof_free_events.push_back(t.stop);
+  }
+  g_prof_launches.clear();
+  return rc;
+}
 
 size_t shotkv_prefill_workspace_bytes(const shotkv_config* cfg, int32_t P, int32_t n_tokens,
                                       int32_t n_shots) {

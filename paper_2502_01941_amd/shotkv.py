@@ -23,8 +23,12 @@ INT32_MAX = 2 ** 31 - 1
 EXPORTS = (
     "shotkv_strerror", "shotkv_abi_version", "shotkv_prefill_workspace_bytes",
     "shotkv_prefill_compress", "shotkv_prefill_scores", "shotkv_select_and_compact",
-    "shotkv_decode_workspace_bytes", "shotkv_decode_step",
+    "shotkv_decode_workspace_bytes", "shotkv_decode_step", "shotkv_profile_enable",
+    "shotkv_profile_read",
 )
+
+KERNEL_KINDS = ("plan", "score", "row_stats", "chunk_mass", "shot_scores", "select", "compact",
+                "decode_partial", "decode_finish")
 
 
 class ShotKVError(RuntimeError):
@@ -76,6 +80,10 @@ def load_library() -> ctypes.CDLL:
     lib.shotkv_decode_step.restype = ctypes.c_int
     lib.shotkv_decode_step.argtypes = [cfgp, i32, ctypes.POINTER(_DecodeState), i32, vp, vp, vp, vp, vp,
                                        vp, vp, vp, sz, vp]
+    lib.shotkv_profile_enable.restype = ctypes.c_int
+    lib.shotkv_profile_enable.argtypes = [ctypes.c_int]
+    lib.shotkv_profile_read.restype = ctypes.c_int
+    lib.shotkv_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64), i32]
     _lib = lib
     return lib
 
@@ -269,3 +277,17 @@ def decode_step(state: DecodeState, step_index: int, q_new, k_new, v_new, want_s
         _ptr(state.workspace), state.workspace.numel(), _stream())
     _check(rc, "shotkv_decode_step")
     return state.out
+
+
+def profile_enable(enable: bool):
+    """shotkv_profile_enable: bracket every kernel launch with HIP events (benchmarks only)."""
+    _check(load_library().shotkv_profile_enable(1 if enable else 0), "shotkv_profile_enable")
+
+
+def profile_read():
+    """shotkv_profile_read: {kernel kind: (total_ms, launches)} since the last read; waits for them."""
+    n = len(KERNEL_KINDS)
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    _check(load_library().shotkv_profile_read(ms, cnt, n), "shotkv_profile_read")
+    return {KERNEL_KINDS[i]: (ms[i], cnt[i]) for i in range(n)}
