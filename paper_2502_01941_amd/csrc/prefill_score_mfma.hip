@@ -7,9 +7,19 @@
 // with v_mfma_f32_32x32x16_bf16.  Keys run along the accumulator registers and queries along the
 // lanes, so the row-softmax statistics (max and sum over keys) are in-lane reductions; only the two
 // lane halves are merged, once per chunk.  K blocks are streamed global -> LDS with 16-byte
-// direct-to-LDS loads (fully coalesced 256-byte rows), double buffered per wave, and read back in MFMA
-// A-operand layout; a 16-byte-slot XOR swizzle keeps those reads free of bank conflicts.  Waves never
-// synchronise with each other.
+// direct-to-LDS loads (whole 256-byte rows, fully coalesced), double buffered per wave, and read back
+// in MFMA A-operand layout.  Waves never synchronise with each other.
+//
+// The direct-to-LDS loads are written as inline assembly and their completion is tracked by hand with
+// s_waitcnt vmcnt: when they are visible to the compiler it makes every LDS read wait for all loads
+// in flight, including the prefetch of the next block, which serialises load and compute.  Unknown
+// vector-memory operations can only make the compiler's own waits stricter, never too weak, because
+// the counter orders completions.
+//
+// LDS layout of a block: key row r starts at r*256 + (r/4)*64 and its 16-byte column c sits in slot
+// c ^ (r%4).  The 64-byte pad per four rows plus the two-bit XOR spread the 16 lanes of a 128-bit LDS
+// read over all banks, while the address of MFMA step ks stays (lane base for ks parity) + 64*(ks/2),
+// i.e. an immediate offset - no per-step address registers.
 #include "common.hpp"
 
 namespace shotkv {
@@ -19,80 +29,100 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) const char lds_cchar;  // keeps LDS reads as ds_read, not flat
 typedef __attribute__((address_space(1))) const void glb_void;
 
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / kWave;
 constexpr int kD = 128;
 constexpr int kBlockKeys = 32;
-constexpr int kRowBytes = kD * 2;                       // 256
-constexpr int kBufBytes = kBlockKeys * kRowBytes;       // 8 KB per wave per buffer
-constexpr int kLoadsPerBlock = kBufBytes / (kWave * 16);  // 8 direct-to-LDS instructions
+constexpr int kRowBytes = kD * 2;                    // 256
+constexpr int kGroupBytes = 4 * kRowBytes + 64;      // four rows + pad = one direct-to-LDS instruction
+constexpr int kLoadsPerBlock = kBlockKeys / 4;       // 8
+constexpr int kBufBytes = kLoadsPerBlock * kGroupBytes;  // 8704 bytes per wave per buffer
 
-// Issue the 8 direct-to-LDS loads of one 32-key block.  LDS slot p (16-byte units) = i*64 + lane
-// holds key row r = p/16, 16-byte column (p%16) ^ (r%16) of that row.  Rows past the end of the chunk
-// re-read its last key (they are masked later), so every address stays inside the chunk.
+// Issue the 8 direct-to-LDS loads of one 32-key block.  Instruction i fills rows 4i..4i+3: lane l
+// writes LDS slot l of the group, which is row 4i + l/16, slot l%16, and therefore fetches column
+// (l%16) ^ (l/16) of that row.  Rows past the end of the chunk re-read its last key (they are masked
+// later), so every address stays inside the chunk.
 __device__ __forceinline__ void issue_block(const char* __restrict__ k_plane, int key0, int rem,
-                                            char* lds_buf, int lane) {
+                                            uint32_t lds_addr, int lane) {
   const int last = rem - 1;  // rem >= 1
+  const int hi = lane >> 4;
+  const uint32_t col_bytes = static_cast<uint32_t>(((lane & 15) ^ hi) << 4);
 #pragma unroll
   for (int i = 0; i < kLoadsPerBlock; ++i) {
-    const int r = i * 4 + (lane >> 4);
-    const int col = (lane & 15) ^ (r & 15);
-    const int rr = min(r, last);
-    const char* src = k_plane + static_cast<size_t>(key0 + rr) * kRowBytes + col * 16;
-    __builtin_amdgcn_global_load_lds((glb_void*)src, (lds_void*)(lds_buf + i * 1024), 16, 0, 0);
+    const int rr = min(4 * i + hi, last);
+    const uint32_t off = static_cast<uint32_t>(key0 + rr) * kRowBytes + col_bytes;
+    // M0 = LDS address of the group (wave-uniform); lane l lands at M0 + 16*l
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr + i * kGroupBytes), "v"(off), "s"(k_plane)
+                 : "memory", "m0");
   }
 }
 
-template <int NQB>
-__device__ __forceinline__ void compute_block(const char* lds_buf, const bf16x8 (&bq)[NQB][8], int lane,
+// Fold the 16 logits a lane holds for one query (key rows 8*(v/4) + 4*half + v%4 of the block) into
+// that query's running (max, sum) in the log2 domain.
+template <bool MASKED>
+__device__ __forceinline__ void softmax_fold(floatx16 acc, float c, int half, int rem, int key0,
+                                             int last_visible, float& m_run, float& l_run) {
+  if (MASKED) {
+    // row 8*(v/4) + v%4 + 4*half is masked when it is past the chunk or past the query's position:
+    // one per-lane limit, compared against compile-time row constants
+    const int limit = min(rem, last_visible - key0 + 1) - 4 * half;
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      if (8 * (v >> 2) + (v & 3) >= limit) acc[v] = -INFINITY;
+  }
+  float bm = fmaxf(acc[0], acc[1]);
+#pragma unroll
+  for (int v = 2; v < 16; v += 2) bm = fmaxf(fmaxf(bm, acc[v]), acc[v + 1]);
+  const float m_new = fmaxf(m_run, bm * c);
+  const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+  const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+  float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+  for (int v = 0; v < 16; v += 2) {
+    s0 += __builtin_amdgcn_exp2f(fmaf(acc[v], c, -m_safe));
+    s1 += __builtin_amdgcn_exp2f(fmaf(acc[v + 1], c, -m_safe));
+  }
+  l_run = l_run * alpha + (s0 + s1);
+  m_run = m_new;
+}
+
+// One 32-key block against all NQB query blocks, two query blocks at a time so that only two
+// accumulator sets are live (the A operands are read from LDS once per pair).
+template <int NQB, bool MASKED>
+__device__ __forceinline__ void compute_block(lds_cchar* lds_buf, const bf16x8 (&bq)[NQB][8], int lane,
                                               int key0, int rem, int causal_base, int W, float c,
                                               float (&m_run)[NQB], float (&l_run)[NQB]) {
-  floatx16 acc[NQB];
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[qb][v] = 0.f;
-
+  constexpr int QG = NQB >= 2 ? 2 : 1;
   const int row = lane & 31, half = lane >> 5;
+  const int base_even = row * kRowBytes + (row >> 2) * 64 + ((half ^ (row & 3)) << 4);
+  lds_cchar* even = lds_buf + base_even;
+  lds_cchar* odd = lds_buf + (base_even ^ 32);
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    const int col = (2 * ks + half) ^ (row & 15);
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(lds_buf + row * kRowBytes + col * 16);
+  for (int grp = 0; grp < NQB / QG; ++grp) {
+    floatx16 acc[QG];
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
-      acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[qb][ks], acc[qb], 0, 0, 0);
-  }
-
-  // accumulator v of this lane is key row 8*(v/4) + 4*half + v%4 of the block, query column `row`
-  const bool ragged = rem < kBlockKeys;
-  const bool in_window = key0 + kBlockKeys - 1 > causal_base;  // causal_base = n_tokens - W
-  if (ragged || in_window) {
+    for (int q = 0; q < QG; ++q)
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      const int j = (qb * 32 + row) % W;
-      const int last_visible = causal_base + j;
+      for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int kr = 8 * (v >> 2) + 4 * half + (v & 3);
-        if (kr >= rem || key0 + kr > last_visible) acc[qb][v] = -INFINITY;
-      }
+    for (int ks = 0; ks < 8; ++ks) {
+      typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
+      const bf16x8 a = *reinterpret_cast<lds_bf16x8*>(((ks & 1) ? odd : even) + 64 * (ks >> 1));
+#pragma unroll
+      for (int q = 0; q < QG; ++q)
+        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[grp * QG + q][ks], acc[q], 0, 0, 0);
     }
-  }
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    float bm = acc[qb][0];
-#pragma unroll
-    for (int v = 1; v < 16; ++v) bm = fmaxf(bm, acc[qb][v]);
-    const float m_new = fmaxf(m_run[qb], bm * c);
-    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_safe);
-    float s = 0.f;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) s += __builtin_amdgcn_exp2f(fmaf(acc[qb][v], c, -m_safe));
-    l_run[qb] = l_run[qb] * alpha + s;
-    m_run[qb] = m_new;
+    for (int q = 0; q < QG; ++q) {
+      const int qb = grp * QG + q;
+      const int last_visible = causal_base + (qb * 32 + row) % W;
+      softmax_fold<MASKED>(acc[q], c, half, rem, key0, last_visible, m_run[qb], l_run[qb]);
+    }
   }
 }
 
@@ -103,9 +133,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_partials_mfma_kernel(
     const int32_t* __restrict__ chunk_len, int max_c, int chunks_per_wave,
     float2* __restrict__ partial) {
   constexpr int R = NQB * 32;
-  // two separately declared buffers so that loads into one are independent of reads from the other
-  __shared__ __attribute__((aligned(16))) char lds_a[kWavesPerBlock][kBufBytes];
-  __shared__ __attribute__((aligned(16))) char lds_b[kWavesPerBlock][kBufBytes];
+  __shared__ __attribute__((aligned(64))) char lds[kWavesPerBlock][2][kBufBytes];
 
   const int lane = threadIdx.x % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -132,21 +160,51 @@ __global__ __launch_bounds__(kThreads, 2) void score_partials_mfma_kernel(
       bq[qb][ks] = *reinterpret_cast<const bf16x8*>(q_rows + (qb * 32 + (lane & 31)) * kD + ks * 16 +
                                                     (lane >> 5) * 8);
 
-  char* buf_a = lds_a[wave];
-  char* buf_b = lds_b[wave];
+  // the query loads must have landed before the streaming loop starts: inside the loop the only
+  // vector-memory operations are the block loads, whose completion is tracked by hand
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" ::"v"(bq[qb][ks]));
+
+  lds_cchar* lds_wave = (lds_cchar*)&lds[wave][0][0];
+  const uint32_t lds_wave_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds_wave));
   const int causal_base = n_tokens - W;
 
   float m_run[NQB], l_run[NQB];
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
 
-  // stream of 32-key blocks over the wave's chunks; `cur` is in flight to / resident in buffer A on
-  // even steps and buffer B on odd steps
+  // A finished chunk's statistics are stored one block later, right after the wait for that block's
+  // data: a store issued just before a wait would have to complete within it (the wait also covers
+  // older stores), this way it has a whole block of compute to do so.  Row r of the partial array is
+  // query lane*NQB + qb; one instruction stores everything (lanes 32..63 carry query blocks 2 and 3).
+  float2 pend[NQB];
+  int pend_c = -1;
+  auto flush = [&]() {
+    float2* dst = out + static_cast<size_t>(pend_c) * R + (lane & 31) * NQB;
+    if (NQB == 4) {
+      const bool upper = lane >= 32;
+      const float2 x = upper ? pend[NQB - 2] : pend[0], y = upper ? pend[NQB - 1] : pend[NQB > 1 ? 1 : 0];
+      *reinterpret_cast<float4*>(dst + (upper ? 2 : 0)) = make_float4(x.x, x.y, y.x, y.y);
+    } else if (NQB == 2) {
+      if (lane < 32) *reinterpret_cast<float4*>(dst) = make_float4(pend[0].x, pend[0].y, pend[NQB - 1].x, pend[NQB - 1].y);
+    } else {
+      if (lane < 32) dst[0] = pend[0];
+    }
+    pend_c = -1;
+  };
+
+  // stream of 32-key blocks over the wave's chunks; `cur` is in flight to / resident in buffer
+  // cur_buf, its successor goes to the other one.  The table entry of the chunk after the current one is
+  // fetched a whole chunk ahead, so stepping into a new chunk never waits on memory.
   int cur_c = c_begin;
-  int cur_key0 = __builtin_amdgcn_readfirstlane(cs[cur_c]);
-  int cur_rem = __builtin_amdgcn_readfirstlane(cl[cur_c]);
-  issue_block(k_plane, cur_key0, cur_rem, buf_a, lane);
-  bool use_a = true;
+  int cur_key0 = cs[cur_c];
+  int cur_rem = cl[cur_c];
+  int ahead_key0 = 0, ahead_len = 0;
+  if (cur_c + 1 < c_end) { ahead_key0 = cs[cur_c + 1]; ahead_len = cl[cur_c + 1]; }
+  issue_block(k_plane, cur_key0, cur_rem, lds_wave_addr, lane);
+  int cur_buf = 0;
 
   while (true) {
     // successor block
@@ -155,56 +213,67 @@ __global__ __launch_bounds__(kThreads, 2) void score_partials_mfma_kernel(
     if (nxt_rem <= 0) {
       nxt_c = cur_c + 1;
       has_next = nxt_c < c_end;
-      if (has_next) {
-        nxt_key0 = __builtin_amdgcn_readfirstlane(cs[nxt_c]);
-        nxt_rem = __builtin_amdgcn_readfirstlane(cl[nxt_c]);
-      }
+      nxt_key0 = ahead_key0;
+      nxt_rem = ahead_len;
+      if (nxt_c + 1 < c_end) { ahead_key0 = cs[nxt_c + 1]; ahead_len = cl[nxt_c + 1]; }
     }
+    // the loads of the next block go out first, then this wave waits only for the older ones
     if (has_next) {
-      issue_block(k_plane, nxt_key0, nxt_rem, use_a ? buf_b : buf_a, lane);
+      issue_block(k_plane, nxt_key0, nxt_rem, lds_wave_addr + (cur_buf ^ 1) * kBufBytes, lane);
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerBlock) : "memory");
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
-    if (use_a)
-      compute_block<NQB>(buf_a, bq, lane, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
+    // keys past the end of the chunk and keys a window query may not see yet are masked; both only
+    // happen in a chunk's last block or in the last W keys, so the common block takes the plain path
+    if (pend_c >= 0) flush();
+    const bool masked = cur_rem < kBlockKeys || cur_key0 + kBlockKeys - 1 > causal_base;
+    if (masked)
+      compute_block<NQB, true>(lds_wave + cur_buf * kBufBytes, bq, lane, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
     else
-      compute_block<NQB>(buf_b, bq, lane, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
+      compute_block<NQB, false>(lds_wave + cur_buf * kBufBytes, bq, lane, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
 
-    if (cur_rem <= kBlockKeys) {  // last block of its chunk: merge the lane halves and emit
+    if (cur_rem <= kBlockKeys) {  // last block of its chunk: merge the lane halves
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb) {
         const float mo = __shfl_xor(m_run[qb], 32, kWave);
         const float lo = __shfl_xor(l_run[qb], 32, kWave);
         const float mn = fmaxf(m_run[qb], mo);
         const float ms = (mn == -INFINITY) ? 0.f : mn;
-        const float l = l_run[qb] * __builtin_amdgcn_exp2f(m_run[qb] - ms) +
-                        lo * __builtin_amdgcn_exp2f(mo - ms);
-        if (lane < 32) out[static_cast<size_t>(cur_c) * R + qb * 32 + lane] = make_float2(mn, l);
+        // a + b is the same in both halves, so lanes l and l+32 now hold identical results
+        pend[qb] = make_float2(mn, l_run[qb] * __builtin_amdgcn_exp2f(m_run[qb] - ms) +
+                                       lo * __builtin_amdgcn_exp2f(mo - ms));
         m_run[qb] = -INFINITY;
         l_run[qb] = 0.f;
       }
+      pend_c = cur_c;
     }
     if (!has_next) break;
     cur_c = nxt_c; cur_key0 = nxt_key0; cur_rem = nxt_rem;
-    use_a = !use_a;
+    cur_buf ^= 1;
   }
+  if (pend_c >= 0) flush();
 }
 
 int pick_chunks_per_wave(const PrefillDims& d, int max_c) {
+#ifdef SHOTKV_CHUNKS_PER_WAVE
+  return SHOTKV_CHUNKS_PER_WAVE;
+#else
   // aim for a few thousand workgroups so that 256 CUs x 2 resident workgroups stay busy, while a wave
   // amortises its query registers over as many chunks as that allows
   const long total_chunks = static_cast<long>(max_c) * d.H_kv * d.P;
   long cpw = total_chunks / (kWavesPerBlock * 4096L);
   if (cpw < 1) cpw = 1;
-  if (cpw > 16) cpw = 16;
+  if (cpw > 8) cpw = 8;
   return static_cast<int>(cpw);
+#endif
 }
 
 }  // namespace
 
 bool score_uses_mfma(const PrefillDims& d) {
-  return d.dtype == SHOTKV_BF16 && d.D == kD && (d.R == 32 || d.R == 64 || d.R == 128);
+  return d.dtype == SHOTKV_BF16 && d.D == kD && (d.R == 32 || d.R == 64 || d.R == 128) &&
+         static_cast<long>(d.n_tokens) * kRowBytes < (1L << 32);
 }
 
 hipError_t launch_score_partials_mfma(const PrefillDims& d, const void* q_obs, const void* k,

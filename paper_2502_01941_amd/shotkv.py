@@ -13,7 +13,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libshotkv.so")
+# SHOTKV_LIBRARY overrides the path (e.g. to load a differently tuned build of the same sources)
+LIB_PATH = os.environ.get("SHOTKV_LIBRARY") or os.path.join(_HERE, "libshotkv.so")
 
 BF16, F32 = 0, 1
 SELECT_PREFIX, SELECT_FIRST_FIT = 0, 1
