@@ -2,24 +2,28 @@
 //
 // Shape: bf16, head_dim 128, R = G*W in {32, 64, 128} query rows per KV head.
 //
-// Work unit = (wave, chunk).  A wave keeps all R x 128 window queries of its KV head in registers as
-// MFMA B operands and walks its chunks in blocks of 32 keys: S^T[32 keys x R queries] = K_blk * Q^T
-// with v_mfma_f32_32x32x16_bf16.  Keys run along the accumulator registers and queries along the
-// lanes, so the row-softmax statistics (max and sum over keys) are in-lane reductions; only the two
-// lane halves are merged, once per chunk.  K blocks are streamed global -> LDS with 16-byte
-// direct-to-LDS loads (whole 256-byte rows, fully coalesced), double buffered per wave, and read back
-// in MFMA A-operand layout.  Waves never synchronise with each other.
+// A workgroup is a pair of waves that walks a range of chunks of one KV head in blocks of 32 keys.
+// Each wave keeps half of the R x 128 window queries in registers as MFMA B operands and computes
+// S^T[32 keys x R/2 queries] = K_blk * Q^T with v_mfma_f32_32x32x16_bf16.  Keys run along the
+// accumulator registers and queries along the lanes, so the row-softmax statistics (max and sum over
+// keys) are in-lane reductions; only the two lane halves are merged, once per chunk.
 //
-// The direct-to-LDS loads are written as inline assembly and their completion is tracked by hand with
-// s_waitcnt vmcnt: when they are visible to the compiler it makes every LDS read wait for all loads
-// in flight, including the prefetch of the next block, which serialises load and compute.  Unknown
-// vector-memory operations can only make the compiler's own waits stricter, never too weak, because
-// the counter orders completions.
+// K blocks are streamed global -> LDS with 16-byte direct-to-LDS loads (whole 256-byte rows, fully
+// coalesced; each wave fetches half of every block) into a ring of three buffers, so two blocks are
+// in flight while one is being consumed; both waves read the whole block back in MFMA A-operand
+// layout.  One s_barrier per block tells the pair that a block has landed and that the buffer of the
+// block before it may be refilled.  With ~150 registers per wave three waves fit on a SIMD.
 //
 // LDS layout of a block: key row r starts at r*256 + (r/4)*64 and its 16-byte column c sits in slot
 // c ^ (r%4).  The 64-byte pad per four rows plus the two-bit XOR spread the 16 lanes of a 128-bit LDS
 // read over all banks, while the address of MFMA step ks stays (lane base for ks parity) + 64*(ks/2),
 // i.e. an immediate offset - no per-step address registers.
+//
+// The direct-to-LDS loads are written as inline assembly and their completion is tracked by hand with
+// s_waitcnt vmcnt: when they are visible to the compiler it makes every LDS read wait for all loads
+// in flight, including the prefetched blocks, which serialises load and compute.  Unknown
+// vector-memory operations can only make the compiler's own waits stricter, never too weak, because
+// loads complete in order.
 #include "common.hpp"
 
 namespace shotkv {
@@ -30,34 +34,34 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(3))) const char lds_cchar;  // keeps LDS reads as ds_read, not flat
-typedef __attribute__((address_space(1))) const void glb_void;
+typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
 
-constexpr int kThreads = 256;
-constexpr int kWavesPerBlock = kThreads / kWave;
 constexpr int kD = 128;
 constexpr int kBlockKeys = 32;
 constexpr int kRowBytes = kD * 2;                    // 256
 constexpr int kGroupBytes = 4 * kRowBytes + 64;      // four rows + pad = one direct-to-LDS instruction
-constexpr int kLoadsPerBlock = kBlockKeys / 4;       // 8
-constexpr int kBufBytes = kLoadsPerBlock * kGroupBytes;  // 8704 bytes per wave per buffer
+constexpr int kGroupsPerBlock = kBlockKeys / 4;      // 8
+constexpr int kBufBytes = kGroupsPerBlock * kGroupBytes;  // 8704 bytes per block
+constexpr int kRing = 3;
 
-// Issue the 8 direct-to-LDS loads of one 32-key block.  Instruction i fills rows 4i..4i+3: lane l
-// writes LDS slot l of the group, which is row 4i + l/16, slot l%16, and therefore fetches column
-// (l%16) ^ (l/16) of that row.  Rows past the end of the chunk re-read its last key (they are masked
-// later), so every address stays inside the chunk.
+// Issue this wave's share of the direct-to-LDS loads of one 32-key block: groups [g0, g0 + NG).
+// Group i fills rows 4i..4i+3: lane l writes LDS slot l of the group, which is row 4i + l/16, slot
+// l%16, and therefore fetches column (l%16) ^ (l/16) of that row.  Rows past the end of the chunk
+// re-read its last key (they are masked later), so every address stays inside the chunk.
+template <int NG>
 __device__ __forceinline__ void issue_block(const char* __restrict__ k_plane, int key0, int rem,
-                                            uint32_t lds_addr, int lane) {
+                                            uint32_t lds_addr, int g0, int lane) {
   const int last = rem - 1;  // rem >= 1
   const int hi = lane >> 4;
   const uint32_t col_bytes = static_cast<uint32_t>(((lane & 15) ^ hi) << 4);
 #pragma unroll
-  for (int i = 0; i < kLoadsPerBlock; ++i) {
-    const int rr = min(4 * i + hi, last);
+  for (int i = 0; i < NG; ++i) {
+    const int rr = min(4 * (g0 + i) + hi, last);
     const uint32_t off = static_cast<uint32_t>(key0 + rr) * kRowBytes + col_bytes;
     // M0 = LDS address of the group (wave-uniform); lane l lands at M0 + 16*l
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_addr + i * kGroupBytes), "v"(off), "s"(k_plane)
+                 : "s"(lds_addr + (g0 + i) * kGroupBytes), "v"(off), "s"(k_plane)
                  : "memory", "m0");
   }
 }
@@ -91,57 +95,60 @@ __device__ __forceinline__ void softmax_fold(floatx16 acc, float c, int half, in
   m_run = m_new;
 }
 
-// One 32-key block against all NQB query blocks, two query blocks at a time so that only two
-// accumulator sets are live (the A operands are read from LDS once per pair).
-template <int NQB, bool MASKED>
-__device__ __forceinline__ void compute_block(lds_cchar* lds_buf, const bf16x8 (&bq)[NQB][8], int lane,
-                                              int key0, int rem, int causal_base, int W, float c,
-                                              float (&m_run)[NQB], float (&l_run)[NQB]) {
-  constexpr int QG = NQB >= 2 ? 2 : 1;
+// One 32-key block against this wave's NQW query blocks (qb0 = index of its first one).
+template <int NQW, bool MASKED>
+__device__ __forceinline__ void compute_block(lds_cchar* lds_buf, const bf16x8 (&bq)[NQW][8], int lane,
+                                              int qb0, int key0, int rem, int causal_base, int W, float c,
+                                              float (&m_run)[NQW], float (&l_run)[NQW]) {
   const int row = lane & 31, half = lane >> 5;
   const int base_even = row * kRowBytes + (row >> 2) * 64 + ((half ^ (row & 3)) << 4);
   lds_cchar* even = lds_buf + base_even;
   lds_cchar* odd = lds_buf + (base_even ^ 32);
+  floatx16 acc[NQW];
 #pragma unroll
-  for (int grp = 0; grp < NQB / QG; ++grp) {
-    floatx16 acc[QG];
+  for (int q = 0; q < NQW; ++q)
 #pragma unroll
-    for (int q = 0; q < QG; ++q)
+    for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
+  for (int ks = 0; ks < 8; ++ks) {
+    const bf16x8 a = *reinterpret_cast<lds_bf16x8*>(((ks & 1) ? odd : even) + 64 * (ks >> 1));
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
-      const bf16x8 a = *reinterpret_cast<lds_bf16x8*>(((ks & 1) ? odd : even) + 64 * (ks >> 1));
+    for (int q = 0; q < NQW; ++q)
+      acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[q][ks], acc[q], 0, 0, 0);
+  }
 #pragma unroll
-      for (int q = 0; q < QG; ++q)
-        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[grp * QG + q][ks], acc[q], 0, 0, 0);
-    }
-#pragma unroll
-    for (int q = 0; q < QG; ++q) {
-      const int qb = grp * QG + q;
-      const int last_visible = causal_base + (qb * 32 + row) % W;
-      softmax_fold<MASKED>(acc[q], c, half, rem, key0, last_visible, m_run[qb], l_run[qb]);
-    }
+  for (int q = 0; q < NQW; ++q) {
+    const int last_visible = causal_base + ((qb0 + q) * 32 + row) % W;
+    softmax_fold<MASKED>(acc[q], c, half, rem, key0, last_visible, m_run[q], l_run[q]);
   }
 }
 
 template <int NQB>
-__global__ __launch_bounds__(kThreads, 2) void score_partials_mfma_kernel(
+struct PairShape {
+  static constexpr int kWaves = NQB >= 2 ? 2 : 1;     // waves per workgroup
+  static constexpr int kNQW = NQB / kWaves;           // query blocks per wave
+  static constexpr int kLoads = kGroupsPerBlock / kWaves;  // load instructions per wave per block
+  static constexpr int kThreads = kWaves * kWave;
+};
+
+template <int NQB>
+__global__ __launch_bounds__(PairShape<NQB>::kThreads, 3) void score_partials_mfma_kernel(
     const bf16_t* __restrict__ q_obs, const bf16_t* __restrict__ k, int n_tokens, int H, int H_kv, int W,
     float c, const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ chunk_start,
-    const int32_t* __restrict__ chunk_len, int max_c, int chunks_per_wave,
+    const int32_t* __restrict__ chunk_len, int max_c, int chunks_per_group,
     float2* __restrict__ partial) {
+  typedef PairShape<NQB> S;
+  constexpr int NQW = S::kNQW;
   constexpr int R = NQB * 32;
-  __shared__ __attribute__((aligned(64))) char lds[kWavesPerBlock][2][kBufBytes];
+  __shared__ __attribute__((aligned(64))) char lds[kRing][kBufBytes];
 
   const int lane = threadIdx.x % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int g = blockIdx.y, p = blockIdx.z;
   const int nc = n_chunks[p];
-  const int c_begin = (blockIdx.x * kWavesPerBlock + wave) * chunks_per_wave;
-  if (c_begin >= nc) return;  // whole wave leaves; there are no workgroup barriers in this kernel
-  const int c_end = min(c_begin + chunks_per_wave, nc);
+  const int c_begin = blockIdx.x * chunks_per_group;
+  if (c_begin >= nc) return;  // the whole workgroup leaves together, before any barrier
+  const int c_end = min(c_begin + chunks_per_group, nc);
 
   const int32_t* cs = chunk_start + static_cast<size_t>(p) * max_c;
   const int32_t* cl = chunk_len + static_cast<size_t>(p) * max_c;
@@ -150,122 +157,139 @@ __global__ __launch_bounds__(kThreads, 2) void score_partials_mfma_kernel(
   const int G = H / H_kv;
   const bf16_t* q_rows = q_obs + (static_cast<size_t>(p) * H + static_cast<size_t>(g) * G) * W * kD;
   float2* out = partial + (static_cast<size_t>(p) * H_kv + g) * max_c * R;
+  const int qb0 = wave * NQW;
 
-  // B operands: query row qb*32 + lane%32, head-dim slice 16*ks + 8*(lane/32) .. +8
-  bf16x8 bq[NQB][8];
+  // B operands: query row (qb0+q)*32 + lane%32, head-dim slice 16*ks + 8*(lane/32) .. +8
+  bf16x8 bq[NQW][8];
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb)
+  for (int q = 0; q < NQW; ++q)
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
-      bq[qb][ks] = *reinterpret_cast<const bf16x8*>(q_rows + (qb * 32 + (lane & 31)) * kD + ks * 16 +
-                                                    (lane >> 5) * 8);
-
+      bq[q][ks] = *reinterpret_cast<const bf16x8*>(q_rows + ((qb0 + q) * 32 + (lane & 31)) * kD + ks * 16 +
+                                                   (lane >> 5) * 8);
   // the query loads must have landed before the streaming loop starts: inside the loop the only
-  // vector-memory operations are the block loads, whose completion is tracked by hand
+  // vector-memory loads are the block loads, whose completion is tracked by hand
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb)
+  for (int q = 0; q < NQW; ++q)
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) asm volatile("" ::"v"(bq[qb][ks]));
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" ::"v"(bq[q][ks]));
 
-  lds_cchar* lds_wave = (lds_cchar*)&lds[wave][0][0];
-  const uint32_t lds_wave_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds_wave));
+  lds_cchar* lds_base = (lds_cchar*)&lds[0][0];
+  const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds_base));
   const int causal_base = n_tokens - W;
+  const int g0 = wave * S::kLoads;
 
-  float m_run[NQB], l_run[NQB];
+  float m_run[NQW], l_run[NQW];
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+  for (int q = 0; q < NQW; ++q) { m_run[q] = -INFINITY; l_run[q] = 0.f; }
 
-  // A finished chunk's statistics are stored one block later, right after the wait for that block's
-  // data: a store issued just before a wait would have to complete within it (the wait also covers
-  // older stores), this way it has a whole block of compute to do so.  Row r of the partial array is
-  // query lane*NQB + qb; one instruction stores everything (lanes 32..63 carry query blocks 2 and 3).
-  float2 pend[NQB];
+  // A finished chunk's statistics are stored one block later, ahead of that iteration's loads: the
+  // wait that follows a store also covers it, so it gets a whole block of compute to complete.  Row
+  // r of the partial array is query (lane%32)*NQB + qb; lanes 0..31 store this wave's query blocks.
+  float2 pend[NQW];
   int pend_c = -1;
   auto flush = [&]() {
-    float2* dst = out + static_cast<size_t>(pend_c) * R + (lane & 31) * NQB;
-    if (NQB == 4) {
-      const bool upper = lane >= 32;
-      const float2 x = upper ? pend[NQB - 2] : pend[0], y = upper ? pend[NQB - 1] : pend[NQB > 1 ? 1 : 0];
-      *reinterpret_cast<float4*>(dst + (upper ? 2 : 0)) = make_float4(x.x, x.y, y.x, y.y);
-    } else if (NQB == 2) {
-      if (lane < 32) *reinterpret_cast<float4*>(dst) = make_float4(pend[0].x, pend[0].y, pend[NQB - 1].x, pend[NQB - 1].y);
-    } else {
-      if (lane < 32) dst[0] = pend[0];
+    float2* dst = out + static_cast<size_t>(pend_c) * R + (lane & 31) * NQB + qb0;
+    if (lane < 32) {
+      if (NQW == 2)
+        *reinterpret_cast<float4*>(dst) = make_float4(pend[0].x, pend[0].y, pend[NQW - 1].x, pend[NQW - 1].y);
+      else
+        dst[0] = pend[0];
     }
     pend_c = -1;
   };
 
-  // stream of 32-key blocks over the wave's chunks; `cur` is in flight to / resident in buffer
-  // cur_buf, its successor goes to the other one.  The table entry of the chunk after the current one is
-  // fetched a whole chunk ahead, so stepping into a new chunk never waits on memory.
-  int cur_c = c_begin;
-  int cur_key0 = cs[cur_c];
-  int cur_rem = cl[cur_c];
-  int ahead_key0 = 0, ahead_len = 0;
-  if (cur_c + 1 < c_end) { ahead_key0 = cs[cur_c + 1]; ahead_len = cl[cur_c + 1]; }
-  issue_block(k_plane, cur_key0, cur_rem, lds_wave_addr, lane);
+  // Stream of 32-key blocks over the workgroup's chunks.  `cur` sits in ring slot cur_buf, `nxt` in
+  // the slot after it, and the block after that is requested as soon as the slot before cur is free.
+  // The table entry of the chunk after the newest requested one is fetched a chunk ahead.
+  int tab_c = c_begin + 1;  // next chunk, whose table entry is already on its way
+  int tab_key0 = 0, tab_len = 0;
+  if (tab_c < c_end) { tab_key0 = cs[tab_c]; tab_len = cl[tab_c]; }
+  int new_c = c_begin, new_key0 = cs[c_begin], new_rem = cl[c_begin];  // newest requested block
+  bool new_valid = true;
+  auto advance = [&]() {  // step (new_*) to its successor block
+    if (new_rem > kBlockKeys) {
+      new_key0 += kBlockKeys;
+      new_rem -= kBlockKeys;
+    } else {
+      new_c = tab_c;
+      new_valid = new_c < c_end;
+      new_key0 = tab_key0;
+      new_rem = tab_len;
+      tab_c = new_c + 1;
+      if (tab_c < c_end) { tab_key0 = cs[tab_c]; tab_len = cl[tab_c]; }
+    }
+  };
+
+  int cur_c = new_c, cur_key0 = new_key0, cur_rem = new_rem;
+  issue_block<S::kLoads>(k_plane, new_key0, new_rem, lds_addr, g0, lane);
+  advance();
+  int nxt_c = new_c, nxt_key0 = new_key0, nxt_rem = new_rem;
+  bool nxt_valid = new_valid;
+  if (nxt_valid) {
+    issue_block<S::kLoads>(k_plane, new_key0, new_rem, lds_addr + kBufBytes, g0, lane);
+    advance();
+  }
   int cur_buf = 0;
 
   while (true) {
-    // successor block
-    int nxt_c = cur_c, nxt_key0 = cur_key0 + kBlockKeys, nxt_rem = cur_rem - kBlockKeys;
-    bool has_next = true;
-    if (nxt_rem <= 0) {
-      nxt_c = cur_c + 1;
-      has_next = nxt_c < c_end;
-      nxt_key0 = ahead_key0;
-      nxt_rem = ahead_len;
-      if (nxt_c + 1 < c_end) { ahead_key0 = cs[nxt_c + 1]; ahead_len = cl[nxt_c + 1]; }
-    }
-    // the loads of the next block go out first, then this wave waits only for the older ones
-    if (has_next) {
-      issue_block(k_plane, nxt_key0, nxt_rem, lds_wave_addr + (cur_buf ^ 1) * kBufBytes, lane);
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerBlock) : "memory");
-    } else {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // this wave's share of `cur` has landed once at most the loads of `nxt` are outstanding ...
+    if (nxt_valid) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(S::kLoads) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // ... and after the barrier so has the partner's; the pair is also done reading the block before
+    if (S::kWaves > 1) asm volatile("s_barrier" ::: "memory");
+    if (pend_c >= 0) flush();
+    const bool req_valid = nxt_valid && new_valid;
+    if (req_valid) {
+      int slot = cur_buf + 2;
+      if (slot >= kRing) slot -= kRing;
+      issue_block<S::kLoads>(k_plane, new_key0, new_rem, lds_addr + slot * kBufBytes, g0, lane);
     }
     // keys past the end of the chunk and keys a window query may not see yet are masked; both only
     // happen in a chunk's last block or in the last W keys, so the common block takes the plain path
-    if (pend_c >= 0) flush();
     const bool masked = cur_rem < kBlockKeys || cur_key0 + kBlockKeys - 1 > causal_base;
     if (masked)
-      compute_block<NQB, true>(lds_wave + cur_buf * kBufBytes, bq, lane, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
+      compute_block<NQW, true>(lds_base + cur_buf * kBufBytes, bq, lane, qb0, cur_key0, cur_rem, causal_base,
+                               W, c, m_run, l_run);
     else
-      compute_block<NQB, false>(lds_wave + cur_buf * kBufBytes, bq, lane, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
+      compute_block<NQW, false>(lds_base + cur_buf * kBufBytes, bq, lane, qb0, cur_key0, cur_rem,
+                                causal_base, W, c, m_run, l_run);
 
     if (cur_rem <= kBlockKeys) {  // last block of its chunk: merge the lane halves
 #pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) {
-        const float mo = __shfl_xor(m_run[qb], 32, kWave);
-        const float lo = __shfl_xor(l_run[qb], 32, kWave);
-        const float mn = fmaxf(m_run[qb], mo);
+      for (int q = 0; q < NQW; ++q) {
+        const float mo = __shfl_xor(m_run[q], 32, kWave);
+        const float lo = __shfl_xor(l_run[q], 32, kWave);
+        const float mn = fmaxf(m_run[q], mo);
         const float ms = (mn == -INFINITY) ? 0.f : mn;
-        // a + b is the same in both halves, so lanes l and l+32 now hold identical results
-        pend[qb] = make_float2(mn, l_run[qb] * __builtin_amdgcn_exp2f(m_run[qb] - ms) +
-                                       lo * __builtin_amdgcn_exp2f(mo - ms));
-        m_run[qb] = -INFINITY;
-        l_run[qb] = 0.f;
+        pend[q] = make_float2(mn, l_run[q] * __builtin_amdgcn_exp2f(m_run[q] - ms) +
+                                      lo * __builtin_amdgcn_exp2f(mo - ms));
+        m_run[q] = -INFINITY;
+        l_run[q] = 0.f;
       }
       pend_c = cur_c;
     }
-    if (!has_next) break;
+    if (!nxt_valid) break;
     cur_c = nxt_c; cur_key0 = nxt_key0; cur_rem = nxt_rem;
-    cur_buf ^= 1;
+    nxt_valid = req_valid;
+    nxt_c = new_c; nxt_key0 = new_key0; nxt_rem = new_rem;
+    if (req_valid) advance();
+    cur_buf = cur_buf + 1 == kRing ? 0 : cur_buf + 1;
   }
   if (pend_c >= 0) flush();
 }
 
-int pick_chunks_per_wave(const PrefillDims& d, int max_c) {
-#ifdef SHOTKV_CHUNKS_PER_WAVE
-  return SHOTKV_CHUNKS_PER_WAVE;
+int pick_chunks_per_group(const PrefillDims& d, int max_c) {
+#ifdef SHOTKV_CHUNKS_PER_GROUP
+  return SHOTKV_CHUNKS_PER_GROUP;
 #else
-  // aim for a few thousand workgroups so that 256 CUs x 2 resident workgroups stay busy, while a wave
+  // enough workgroups to keep 256 CUs x 6 resident pairs busy several times over, while a pair
   // amortises its query registers over as many chunks as that allows
   const long total_chunks = static_cast<long>(max_c) * d.H_kv * d.P;
-  long cpw = total_chunks / (kWavesPerBlock * 4096L);
-  if (cpw < 1) cpw = 1;
-  if (cpw > 8) cpw = 8;
-  return static_cast<int>(cpw);
+  long cpg = total_chunks / 16384L;
+  if (cpg < 1) cpg = 1;
+  if (cpg > 8) cpg = 8;
+  return static_cast<int>(cpg);
 #endif
 }
 
@@ -278,14 +302,14 @@ bool score_uses_mfma(const PrefillDims& d) {
 
 hipError_t launch_score_partials_mfma(const PrefillDims& d, const void* q_obs, const void* k,
                                       const PrefillWorkspace& w, hipStream_t s) {
-  const int cpw = pick_chunks_per_wave(d, w.max_c);
-  const dim3 grid(ceil_div(w.max_c, kWavesPerBlock * cpw), d.H_kv, d.P), block(kThreads);
+  const int cpg = pick_chunks_per_group(d, w.max_c);
+  const dim3 grid(ceil_div(w.max_c, cpg), d.H_kv, d.P);
   const float c = d.sm_scale * kLog2e;
   KernelTimer timer(kKernelScore, s);
 #define SHOTKV_LAUNCH_SCORE(NQB)                                                                      \
-  hipLaunchKernelGGL(score_partials_mfma_kernel<NQB>, grid, block, 0, s,                              \
+  hipLaunchKernelGGL(score_partials_mfma_kernel<NQB>, grid, dim3(PairShape<NQB>::kThreads), 0, s,     \
                      static_cast<const bf16_t*>(q_obs), static_cast<const bf16_t*>(k), d.n_tokens, d.H, \
-                     d.H_kv, d.W, c, w.n_chunks, w.chunk_start, w.chunk_len, w.max_c, cpw, w.partial)
+                     d.H_kv, d.W, c, w.n_chunks, w.chunk_start, w.chunk_len, w.max_c, cpg, w.partial)
   switch (d.R / 32) {
     case 1: SHOTKV_LAUNCH_SCORE(1); break;
     case 2: SHOTKV_LAUNCH_SCORE(2); break;
