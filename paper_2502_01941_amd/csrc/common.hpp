@@ -79,11 +79,6 @@ struct PrefillWorkspace {
   float2*  row_stat;      // [P][H_kv][R]  (global max, 1 / global sum)
   float*   chunk_mass;    // [P][maxC]
   float*   scores;        // [P][n_shots]
-  // copy plan
-  int32_t* n_runs;        // [P]
-  int32_t* run_src;       // [P][n_shots+2]
-  int32_t* run_dst;       // [P][n_shots+2]
-  int32_t* run_len;       // [P][n_shots+2]
   int32_t  max_c;
   int32_t  chunk_keys;
   size_t   bytes;
@@ -112,10 +107,6 @@ inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_
   w.row_stat = reinterpret_cast<float2*>(take(P_ * H_kv * R * 8));
   w.chunk_mass = reinterpret_cast<float*>(take(P_ * C * 4));
   w.scores = reinterpret_cast<float*>(take(P_ * S * 4 + 4));
-  w.n_runs = reinterpret_cast<int32_t*>(take(P_ * 4));
-  w.run_src = reinterpret_cast<int32_t*>(take(P_ * (S + 2) * 4));
-  w.run_dst = reinterpret_cast<int32_t*>(take(P_ * (S + 2) * 4));
-  w.run_len = reinterpret_cast<int32_t*>(take(P_ * (S + 2) * 4));
   w.bytes = off;
   return w;
 }
@@ -139,10 +130,10 @@ hipError_t launch_reduce_scores(const PrefillDims& d, const int32_t* shot_offset
 hipError_t launch_select_plan(const PrefillDims& d, const float* shot_scores,
                               const int32_t* shot_offsets, const int32_t* budget_tokens, int cap,
                               int32_t* kept_count, uint8_t* shot_selected, int32_t* status,
-                              const PrefillWorkspace& w, hipStream_t s);
+                              int32_t* kept_positions, hipStream_t s);
 hipError_t launch_compact(const PrefillDims& d, const void* k, const void* v, void* k_out, void* v_out,
-                          int cap, int32_t* kept_positions, const int32_t* kept_count,
-                          const PrefillWorkspace& w, hipStream_t s);
+                          int cap, const int32_t* kept_positions, const int32_t* kept_count,
+                          hipStream_t s);
 
 bool score_uses_mfma(const PrefillDims& d);
 

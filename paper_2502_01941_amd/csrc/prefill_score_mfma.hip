@@ -129,10 +129,12 @@ struct PairShape {
   static constexpr int kNQW = NQB / kWaves;           // query blocks per wave
   static constexpr int kLoads = kGroupsPerBlock / kWaves;  // load instructions per wave per block
   static constexpr int kThreads = kWaves * kWave;
+  static constexpr int kMinWavesPerSimd = kWaves > 1 ? 3 : 1;  // single-wave groups are LDS-limited
 };
 
 template <int NQB>
-__global__ __launch_bounds__(PairShape<NQB>::kThreads, 3) void score_partials_mfma_kernel(
+__global__ __launch_bounds__(PairShape<NQB>::kThreads, PairShape<NQB>::kMinWavesPerSimd) void
+score_partials_mfma_kernel(
     const bf16_t* __restrict__ q_obs, const bf16_t* __restrict__ k, int n_tokens, int H, int H_kv, int W,
     float c, const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ chunk_start,
     const int32_t* __restrict__ chunk_len, int max_c, int chunks_per_group,

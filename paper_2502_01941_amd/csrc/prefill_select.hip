@@ -2,7 +2,8 @@
 // (Section 5.1, Eq. 5-6; Algorithm 1 phase 1: rank by score, keep shots in descending order while the
 // budget holds).  One workgroup per problem; ranking is a bitonic sort in LDS on the key
 // (score descending, shot index ascending), the budget walk is a prefix sum of shot lengths in rank
-// order, and the copy plan is a prefix sum of kept lengths in position order.
+// order, and the copy plan - the original position of every retained row, ascending - comes from a
+// prefix sum of kept lengths in position order.
 #include "common.hpp"
 
 namespace shotkv {
@@ -46,20 +47,16 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
     const float* __restrict__ shot_scores, const int32_t* __restrict__ shot_offsets,
     const int32_t* __restrict__ budget_tokens, int n_shots, int n_tokens, int window, int cap,
     int select_mode, int32_t* __restrict__ kept_count, uint8_t* __restrict__ shot_selected,
-    int32_t* __restrict__ status, int32_t* __restrict__ n_runs, int32_t* __restrict__ run_src,
-    int32_t* __restrict__ run_dst, int32_t* __restrict__ run_len) {
+    int32_t* __restrict__ status, int32_t* __restrict__ kept_positions) {
   const int p = blockIdx.x, tid = threadIdx.x;
   const int32_t* off = shot_offsets + static_cast<size_t>(p) * (n_shots + 1);
   const float* scores = shot_scores + static_cast<size_t>(p) * n_shots;
   uint8_t* sel = shot_selected ? shot_selected + static_cast<size_t>(p) * n_shots : nullptr;
-  int32_t* r_src = run_src + static_cast<size_t>(p) * (n_shots + 2);
-  int32_t* r_dst = run_dst + static_cast<size_t>(p) * (n_shots + 2);
-  int32_t* r_len = run_len + static_cast<size_t>(p) * (n_shots + 2);
+  int32_t* kept_pos = kept_positions + static_cast<size_t>(p) * cap;
 
   __shared__ float s_score[SHOTKV_MAX_SHOTS];
   __shared__ uint16_t s_idx[SHOTKV_MAX_SHOTS];
   __shared__ int s_a[SHOTKV_MAX_SHOTS + 2];    // scan array
-  __shared__ int s_b[SHOTKV_MAX_SHOTS + 2];    // second scan array (run counts)
   __shared__ uint8_t s_keep[SHOTKV_MAX_SHOTS];
   __shared__ int s_tmp[kSelThreads];
   __shared__ int s_flag;
@@ -84,7 +81,7 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
     if (shot_budget < 0) st = SHOTKV_ST_BUDGET_TOO_SMALL;
   }
   if (st != SHOTKV_ST_OK) {
-    if (tid == 0) { status[p] = st; kept_count[p] = 0; n_runs[p] = 0; }
+    if (tid == 0) { status[p] = st; kept_count[p] = 0; }
     if (sel) for (int i = tid; i < n_shots; i += kSelThreads) sel[i] = 0;
     return;
   }
@@ -143,32 +140,27 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
 
   // ---- copy plan in position order: segment 0 = prefix, 1..n = shots, n+1 = tail ----------------
   const int n_seg = n_shots + 2;
+  auto segment = [&](int s, int& src, int& len) {
+    if (s == 0) { src = 0; len = n_prefix; }
+    else if (s == n_seg - 1) { src = off[n_shots]; len = n_tail; }
+    else { src = off[s - 1]; len = s_keep[s - 1] ? (off[s] - off[s - 1]) : 0; }
+  };
   for (int s = tid; s < n_seg; s += kSelThreads) {
-    int len;
-    if (s == 0) len = n_prefix;
-    else if (s == n_seg - 1) len = n_tail;
-    else len = s_keep[s - 1] ? (off[s] - off[s - 1]) : 0;
+    int src, len;
+    segment(s, src, len);
     s_a[s] = len;
-    s_b[s] = len > 0 ? 1 : 0;
   }
   __syncthreads();
-  // lengths are needed again after the scan: recompute them rather than keep a third array
-  const int total = block_exclusive_scan(s_a, n_seg, s_tmp);
-  const int runs = block_exclusive_scan(s_b, n_seg, s_tmp);
-  for (int s = tid; s < n_seg; s += kSelThreads) {
-    int len, src;
-    if (s == 0) { len = n_prefix; src = 0; }
-    else if (s == n_seg - 1) { len = n_tail; src = off[n_shots]; }
-    else { len = s_keep[s - 1] ? (off[s] - off[s - 1]) : 0; src = off[s - 1]; }
-    if (len > 0) {
-      const int slot = s_b[s];
-      r_src[slot] = src;
-      r_dst[slot] = s_a[s];
-      r_len[slot] = len;
-    }
+  const int total = block_exclusive_scan(s_a, n_seg, s_tmp);  // s_a[s] = first output row of segment s
+  // every retained row's original position; one wave per segment, lanes along the rows
+  for (int s = tid / kWave; s < n_seg; s += kSelThreads / kWave) {
+    int src, len;
+    segment(s, src, len);
+    const int dst = s_a[s];
+    for (int i = tid % kWave; i < len; i += kWave) kept_pos[dst + i] = src + i;
   }
   if (sel) for (int i = tid; i < n_shots; i += kSelThreads) sel[i] = s_keep[i];
-  if (tid == 0) { status[p] = SHOTKV_ST_OK; kept_count[p] = total; n_runs[p] = runs; }
+  if (tid == 0) { status[p] = SHOTKV_ST_OK; kept_count[p] = total; }
 }
 
 }  // namespace
@@ -176,11 +168,11 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
 hipError_t launch_select_plan(const PrefillDims& d, const float* shot_scores,
                               const int32_t* shot_offsets, const int32_t* budget_tokens, int cap,
                               int32_t* kept_count, uint8_t* shot_selected, int32_t* status,
-                              const PrefillWorkspace& w, hipStream_t s) {
+                              int32_t* kept_positions, hipStream_t s) {
   KernelTimer timer(kKernelSelect, s);
   hipLaunchKernelGGL(select_plan_kernel, dim3(d.P), dim3(kSelThreads), 0, s, shot_scores, shot_offsets,
                      budget_tokens, d.n_shots, d.n_tokens, d.W, cap, d.select_mode, kept_count,
-                     shot_selected, status, w.n_runs, w.run_src, w.run_dst, w.run_len);
+                     shot_selected, status, kept_positions);
   return hipGetLastError();
 }
 

@@ -186,8 +186,8 @@ int shotkv_select_and_compact(const shotkv_config* cfg, int32_t P, int32_t n_tok
   if (workspace_bytes < w.bytes) return SHOTKV_E_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = launch_select_plan(d, shot_scores, shot_offsets, budget_tokens, cap, kept_count,
-                                    shot_selected, status, w, s);
-  if (e == hipSuccess) e = launch_compact(d, k, v, k_out, v_out, cap, kept_positions, kept_count, w, s);
+                                    shot_selected, status, kept_positions, s);
+  if (e == hipSuccess) e = launch_compact(d, k, v, k_out, v_out, cap, kept_positions, kept_count, s);
   return from_hip(e);
 }
 
@@ -216,8 +216,8 @@ int shotkv_prefill_compress(const shotkv_config* cfg, int32_t P, int32_t n_token
   if (e == hipSuccess) e = launch_reduce_scores(d, shot_offsets, status, scores, w, s);
   if (e == hipSuccess)
     e = launch_select_plan(d, scores, shot_offsets, budget_tokens, cap, kept_count, shot_selected,
-                           status, w, s);
-  if (e == hipSuccess) e = launch_compact(d, k, v, k_out, v_out, cap, kept_positions, kept_count, w, s);
+                           status, kept_positions, s);
+  if (e == hipSuccess) e = launch_compact(d, k, v, k_out, v_out, cap, kept_positions, kept_count, s);
   return from_hip(e);
 }
 
