@@ -5,18 +5,31 @@
 //                  once with 16-byte lanes, and keeps an online softmax (max, sum, weighted V) per
 //                  query head of the group.  It also appends k_new/v_new to the chosen free slot and
 //                  records the scaled logits of decode tokens for the retention score.
-// decode_finish  : merges the splits, writes the attention output, forms Score(t) = sum_h alpha_{t,h}
-//                  for decode tokens (Eq. 7) and evicts the lowest-scored earlier token when the
-//                  decode cache exceeds its budget (Eq. 8 in capacity form).
+// decode_merge   : one workgroup per (sequence, KV head) merges the splits of its query heads, writes
+//                  their attention output and the heads' share of Score(t) = sum_h alpha_{t,h} for
+//                  the decode tokens (Eq. 7).
+// decode_retain  : one workgroup per sequence adds the shares in fixed order and evicts the
+//                  lowest-scored earlier token when the decode cache exceeds its budget (Eq. 8 in
+//                  capacity form).  (A kernel boundary is cheaper here than a device-scope fence:
+//                  the workgroups of a sequence sit on different XCDs with separate L2 caches.)
 #include "common.hpp"
 
 namespace shotkv {
 
 namespace {
 
-constexpr int kDecThreads = 256;
+#ifndef SHOTKV_DEC_THREADS
+#define SHOTKV_DEC_THREADS 256
+#endif
+#ifndef SHOTKV_DEC_UNROLL
+#define SHOTKV_DEC_UNROLL 1
+#endif
+#ifndef SHOTKV_DEC_TARGET_GROUPS
+#define SHOTKV_DEC_TARGET_GROUPS 1024
+#endif
+constexpr int kDecThreads = SHOTKV_DEC_THREADS;
 constexpr int kDecWaves = kDecThreads / kWave;
-constexpr int kUnroll = 4;
+constexpr int kUnroll = SHOTKV_DEC_UNROLL;  // tokens a lane group has in flight
 
 // lowest free slot of a sequence, -1 if none; every thread of the block gets the answer
 __device__ int find_free_slot(const int32_t* __restrict__ slot_pos, int n_slots, int* s_red) {
@@ -59,7 +72,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     const int32_t* __restrict__ slot_pos, int cap, int n_slots, int H, int H_kv, int n_splits,
     int split_tokens, float scale_log2e, const T* __restrict__ q_new, const T* __restrict__ k_new,
     const T* __restrict__ v_new, float2* __restrict__ part_ml, float* __restrict__ part_o,
-    float* __restrict__ z_dec) {
+    float* __restrict__ z_dec, int32_t* __restrict__ new_slot_out) {
   constexpr int E = Vec16<T>::kElems;       // elements per 16-byte lane
   constexpr int LPR = D / E;                // lanes per K/V row
   constexpr int GPW = kWave / LPR;          // token groups per wave
@@ -75,8 +88,14 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
   __shared__ float s_o[kDecWaves][G][D];
 
   const int32_t* sp = slot_pos + static_cast<size_t>(s) * n_slots;
-  const int new_slot = find_free_slot(sp, n_slots, s_red);
   const int pc = min(prefill_count[s], cap);
+  const int t_begin = split * split_tokens;
+  const int t_end = min(t_begin + split_tokens, pc + n_slots);
+  // only a range that reaches into the decode slots needs to know which slot takes the new token;
+  // ranges of prefill rows start streaming at once (if the pool turns out to be full their partials
+  // are simply not used)
+  const int new_slot = (t_end > pc) ? find_free_slot(sp, n_slots, s_red) : n_slots;
+  if (t_end > pc && g == 0 && tid == 0 && t_end == pc + n_slots) new_slot_out[s] = new_slot;
 
   float m[G], l[G], o[G][E], q[G][E];
 #pragma unroll
@@ -93,8 +112,6 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
   const size_t plane_p = (static_cast<size_t>(s) * H_kv + g) * cap;
   const size_t plane_d = (static_cast<size_t>(s) * H_kv + g) * n_slots;
   const size_t new_off = (static_cast<size_t>(s) * H_kv + g) * D;
-  const int t_begin = split * split_tokens;
-  const int t_end = min(t_begin + split_tokens, pc + n_slots);
 
   if (new_slot >= 0) {
     for (int t0 = t_begin + grp; t0 < t_end; t0 += NG * kUnroll) {
@@ -163,12 +180,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) mn = fmaxf(mn, z[u][h]);
         if (mn == -INFINITY) continue;  // nothing valid yet for this group
-        const float alpha = exp2f(m[h] - mn);
+        const float alpha = __builtin_amdgcn_exp2f(m[h] - mn);
         float pw[kUnroll];
         float psum = 0.f;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-          pw[u] = exp2f(z[u][h] - mn);
+          pw[u] = __builtin_amdgcn_exp2f(z[u][h] - mn);
           psum += pw[u];
         }
         l[h] = l[h] * alpha + psum;
@@ -236,25 +253,81 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
 }
 
 constexpr int kFinThreads = 256;
+constexpr int kFinWaves = kFinThreads / kWave;
 
-__global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
+// lower score first, then the newer token: the order in which decode tokens are evicted
+__device__ __forceinline__ bool evict_before(float sa, int pa, float sb, int pb) {
+  return sa < sb || (sa == sb && pa > pb);
+}
+
+__global__ __launch_bounds__(kFinThreads) void decode_merge_kernel(
     const float2* __restrict__ part_ml, const float* __restrict__ part_o,
-    const float* __restrict__ z_dec, int32_t* __restrict__ slot_pos, int n_slots, int H, int D,
-    int n_splits, int budget, int step_index, float* __restrict__ out,
+    const float* __restrict__ z_dec, const int32_t* __restrict__ slot_pos,
+    const int32_t* __restrict__ new_slot_in, int n_slots, int H, int H_kv, int D, int n_splits,
+    float* __restrict__ out, float* __restrict__ score_part) {
+  const int g = blockIdx.x, s = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid % kWave, wave = tid / kWave;
+  const int G = H / H_kv;
+  __shared__ float s_M[8];
+  __shared__ float s_invL[8];
+
+  const int32_t* sp = slot_pos + static_cast<size_t>(s) * n_slots;
+  const int new_slot = new_slot_in[s];
+  const size_t head0 = static_cast<size_t>(s) * H + static_cast<size_t>(g) * G;
+  if (new_slot < 0) {  // pool full: the step is void for this sequence
+    for (int i = tid; i < G * D; i += kFinThreads) out[head0 * D + i] = 0.f;
+    return;
+  }
+
+  // global softmax statistics of this group's heads: one wave per head, lanes over the splits
+  for (int hl = wave; hl < G; hl += kFinWaves) {
+    const float2* ml = part_ml + (head0 + hl) * n_splits;
+    float m = -INFINITY, l = 0.f;
+    if (lane < n_splits) { const float2 x = ml[lane]; m = x.x; l = x.y; }
+    const float M = wave_max(m);
+    const float L = wave_sum(l > 0.f ? l * __builtin_amdgcn_exp2f(m - M) : 0.f);
+    if (lane == 0) { s_M[hl] = M; s_invL[hl] = 1.f / L; }
+  }
+  __syncthreads();
+
+  for (int idx = tid; idx < G * D; idx += kFinThreads) {
+    const int hl = idx / D, dd = idx % D;
+    const float2* ml = part_ml + (head0 + hl) * n_splits;
+    const float* po = part_o + (head0 + hl) * n_splits * D + dd;
+    float acc = 0.f;
+    for (int i = 0; i < n_splits; ++i) {
+      const float2 x = ml[i];
+      if (x.y > 0.f) acc += po[static_cast<size_t>(i) * D] * __builtin_amdgcn_exp2f(x.x - s_M[hl]);
+    }
+    out[(head0 + hl) * D + dd] = acc * s_invL[hl];
+  }
+
+  // this group's share of the retention scores
+  float* part = score_part + (static_cast<size_t>(s) * H_kv + g) * n_slots;
+  for (int slot = tid; slot < n_slots; slot += kFinThreads) {
+    float share = 0.f;
+    if (slot == new_slot || sp[slot] >= 0) {
+      for (int hl = 0; hl < G; ++hl)
+        share += __builtin_amdgcn_exp2f(z_dec[(head0 + hl) * n_slots + slot] - s_M[hl]) * s_invL[hl];
+    }
+    part[slot] = share;
+  }
+}
+
+__global__ __launch_bounds__(kFinThreads) void decode_retain_kernel(
+    const float* __restrict__ score_part, int32_t* __restrict__ slot_pos,
+    const int32_t* __restrict__ new_slot_in, int n_slots, int H_kv, int budget, int step_index,
     float* __restrict__ token_scores, int32_t* __restrict__ evicted_pos, int32_t* __restrict__ status) {
   const int s = blockIdx.x, tid = threadIdx.x;
-  __shared__ int s_red[kFinThreads / kWave];
-  __shared__ float s_M[64];
-  __shared__ float s_invL[64];
-  __shared__ float s_best_score[kFinThreads / kWave];
-  __shared__ int s_best_pos[kFinThreads / kWave];
-  __shared__ int s_best_slot[kFinThreads / kWave];
-  __shared__ int s_count[kFinThreads / kWave];
+  const int lane = tid % kWave, wave = tid / kWave;
+  __shared__ float s_best_score[kFinWaves];
+  __shared__ int s_best_pos[kFinWaves];
+  __shared__ int s_best_slot[kFinWaves];
+  __shared__ int s_count[kFinWaves];
 
   int32_t* sp = slot_pos + static_cast<size_t>(s) * n_slots;
-  const int new_slot = find_free_slot(sp, n_slots, s_red);
+  const int new_slot = new_slot_in[s];
   if (new_slot < 0) {
-    for (int i = tid; i < H * D; i += kFinThreads) out[static_cast<size_t>(s) * H * D + i] = 0.f;
     if (token_scores)
       for (int i = tid; i < n_slots; i += kFinThreads) token_scores[static_cast<size_t>(s) * n_slots + i] = 0.f;
     if (tid == 0) {
@@ -264,39 +337,16 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
     return;
   }
 
-  if (tid < H) {
-    const float2* ml = part_ml + (static_cast<size_t>(s) * H + tid) * n_splits;
-    float M = -INFINITY;
-    for (int i = 0; i < n_splits; ++i) M = fmaxf(M, ml[i].x);
-    float L = 0.f;
-    for (int i = 0; i < n_splits; ++i)
-      if (ml[i].y > 0.f) L += ml[i].y * exp2f(ml[i].x - M);
-    s_M[tid] = M;
-    s_invL[tid] = 1.f / L;
-  }
-  __syncthreads();
-
-  for (int idx = tid; idx < H * D; idx += kFinThreads) {
-    const int h = idx / D, dd = idx % D;
-    const float2* ml = part_ml + (static_cast<size_t>(s) * H + h) * n_splits;
-    const float* po = part_o + (static_cast<size_t>(s) * H + h) * n_splits * D + dd;
-    float acc = 0.f;
-    for (int i = 0; i < n_splits; ++i)
-      if (ml[i].y > 0.f) acc += po[static_cast<size_t>(i) * D] * exp2f(ml[i].x - s_M[h]);
-    out[static_cast<size_t>(s) * H * D + idx] = acc * s_invL[h];
-  }
-
-  // retention scores and the eviction candidate: lowest score, then newest token
   float best_score = INFINITY;
   int best_pos = -1, best_slot = -1, count = 0;
+  const float* parts = score_part + static_cast<size_t>(s) * H_kv * n_slots;
   for (int slot = tid; slot < n_slots; slot += kFinThreads) {
     const int pos = (slot == new_slot) ? step_index : sp[slot];
     float score = 0.f;
     if (pos >= 0) {
       ++count;
-      for (int h = 0; h < H; ++h)
-        score += exp2f(z_dec[(static_cast<size_t>(s) * H + h) * n_slots + slot] - s_M[h]) * s_invL[h];
-      if (slot != new_slot && (score < best_score || (score == best_score && pos > best_pos))) {
+      for (int gg = 0; gg < H_kv; ++gg) score += parts[static_cast<size_t>(gg) * n_slots + slot];
+      if (slot != new_slot && (best_slot < 0 || evict_before(score, pos, best_score, best_pos))) {
         best_score = score; best_pos = pos; best_slot = slot;
       }
     }
@@ -307,21 +357,21 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
     const int op = __shfl_xor(best_pos, o, kWave);
     const int ol = __shfl_xor(best_slot, o, kWave);
     count += __shfl_xor(count, o, kWave);
-    if (ol >= 0 && (best_slot < 0 || os < best_score || (os == best_score && op > best_pos))) {
+    if (ol >= 0 && (best_slot < 0 || evict_before(os, op, best_score, best_pos))) {
       best_score = os; best_pos = op; best_slot = ol;
     }
   }
-  if (tid % kWave == 0) {
-    s_best_score[tid / kWave] = best_score; s_best_pos[tid / kWave] = best_pos;
-    s_best_slot[tid / kWave] = best_slot; s_count[tid / kWave] = count;
+  if (lane == 0) {
+    s_best_score[wave] = best_score; s_best_pos[wave] = best_pos;
+    s_best_slot[wave] = best_slot; s_count[wave] = count;
   }
   __syncthreads();
   if (tid == 0) {
     int total = s_count[0];  // this thread already holds wave 0's candidate
-    for (int w = 1; w < kFinThreads / kWave; ++w) {
+    for (int w = 1; w < kFinWaves; ++w) {
       total += s_count[w];
-      if (s_best_slot[w] >= 0 && (best_slot < 0 || s_best_score[w] < best_score ||
-                                  (s_best_score[w] == best_score && s_best_pos[w] > best_pos))) {
+      if (s_best_slot[w] >= 0 &&
+          (best_slot < 0 || evict_before(s_best_score[w], s_best_pos[w], best_score, best_pos))) {
         best_score = s_best_score[w]; best_pos = s_best_pos[w]; best_slot = s_best_slot[w];
       }
     }
@@ -339,12 +389,13 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
 }  // namespace
 
 int decode_splits(int S, int H_kv, int total_tokens) {
-  // enough workgroups to cover the 256 CUs a few times over, but at least 256 tokens per split
+  // enough workgroups to fill 256 CUs several times over, but no split shorter than 128 tokens and
+  // no more splits than one wave can merge
   const int pairs = S * H_kv;
-  int splits = ceil_div(1024, pairs);
-  const int max_by_tokens = total_tokens / 256 > 0 ? total_tokens / 256 : 1;
+  int splits = ceil_div(SHOTKV_DEC_TARGET_GROUPS, pairs);
+  const int max_by_tokens = total_tokens / 128 > 0 ? total_tokens / 128 : 1;
   if (splits > max_by_tokens) splits = max_by_tokens;
-  if (splits > 64) splits = 64;
+  if (splits > kWave) splits = kWave;
   if (splits < 1) splits = 1;
   return splits;
 }
@@ -362,7 +413,7 @@ static hipError_t launch_partial_g(const DecodeDims& d, const shotkv_decode_stat
                      st.prefill_count, static_cast<T*>(st.k_dec), static_cast<T*>(st.v_dec),           \
                      st.slot_pos, d.cap, d.n_slots, d.H, d.H_kv, d.n_splits, d.split_tokens, c,         \
                      static_cast<const T*>(q_new), static_cast<const T*>(k_new),                       \
-                     static_cast<const T*>(v_new), w.part_ml, w.part_o, w.z_dec)
+                     static_cast<const T*>(v_new), w.part_ml, w.part_o, w.z_dec, w.new_slot)
   switch (d.G) {
     case 1: SHOTKV_LAUNCH_DEC(1); break;
     case 2: SHOTKV_LAUNCH_DEC(2); break;
@@ -390,10 +441,18 @@ hipError_t launch_decode_partial(const DecodeDims& d, const shotkv_decode_state&
 hipError_t launch_decode_finish(const DecodeDims& d, const shotkv_decode_state& st, float* out,
                                 float* token_scores, int32_t* evicted_pos, int32_t* status,
                                 const DecodeWorkspace& w, hipStream_t s) {
-  KernelTimer timer(kKernelDecodeFinish, s);
-  hipLaunchKernelGGL(decode_finish_kernel, dim3(d.S), dim3(kFinThreads), 0, s, w.part_ml, w.part_o,
-                     w.z_dec, st.slot_pos, d.n_slots, d.H, d.D, d.n_splits, d.budget, d.step, out,
-                     token_scores, evicted_pos, status);
+  {
+    KernelTimer timer(kKernelDecodeFinish, s);
+    hipLaunchKernelGGL(decode_merge_kernel, dim3(d.H_kv, d.S), dim3(kFinThreads), 0, s, w.part_ml,
+                       w.part_o, w.z_dec, st.slot_pos, w.new_slot, d.n_slots, d.H, d.H_kv, d.D,
+                       d.n_splits, out, w.score_part);
+  }
+  {
+    KernelTimer timer(kKernelDecodeFinish, s);
+    hipLaunchKernelGGL(decode_retain_kernel, dim3(d.S), dim3(kFinThreads), 0, s, w.score_part,
+                       st.slot_pos, w.new_slot, d.n_slots, d.H_kv, d.budget, d.step, token_scores,
+                       evicted_pos, status);
+  }
   return hipGetLastError();
 }
 

@@ -237,7 +237,7 @@ static int make_decode_dims(const shotkv_config* cfg, int S, int cap, int n_slot
 size_t shotkv_decode_workspace_bytes(const shotkv_config* cfg, int32_t S, int32_t cap, int32_t n_slots) {
   DecodeDims d;
   if (make_decode_dims(cfg, S, cap, n_slots, &d) != SHOTKV_OK) return 0;
-  return carve_decode(nullptr, d.S, d.H, d.D, d.n_slots, d.n_splits).bytes;
+  return carve_decode(nullptr, d.S, d.H, d.H_kv, d.D, d.n_slots, d.n_splits).bytes;
 }
 
 int shotkv_decode_step(const shotkv_config* cfg, int32_t S, const shotkv_decode_state* st,
@@ -256,7 +256,7 @@ int shotkv_decode_step(const shotkv_config* cfg, int32_t S, const shotkv_decode_
       !aligned16(st->v_dec) || !aligned16(q_new) || !aligned16(k_new) || !aligned16(v_new) ||
       !aligned16(workspace))
     return SHOTKV_E_ALIGN;
-  const DecodeWorkspace w = carve_decode(workspace, d.S, d.H, d.D, d.n_slots, d.n_splits);
+  const DecodeWorkspace w = carve_decode(workspace, d.S, d.H, d.H_kv, d.D, d.n_slots, d.n_splits);
   if (workspace_bytes < w.bytes) return SHOTKV_E_WORKSPACE;
   d.budget = st->decode_budget;
   d.step = step_index;
