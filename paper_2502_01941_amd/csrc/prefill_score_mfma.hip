@@ -42,7 +42,14 @@ constexpr int kRowBytes = kD * 2;                    // 256
 constexpr int kGroupBytes = 4 * kRowBytes + 64;      // four rows + pad = one direct-to-LDS instruction
 constexpr int kGroupsPerBlock = kBlockKeys / 4;      // 8
 constexpr int kBufBytes = kGroupsPerBlock * kGroupBytes;  // 8704 bytes per block
-constexpr int kRing = 3;
+#ifndef SHOTKV_SCORE_RING
+#define SHOTKV_SCORE_RING 3
+#endif
+#ifndef SHOTKV_SCORE_WAVES_PER_SIMD
+#define SHOTKV_SCORE_WAVES_PER_SIMD 3
+#endif
+constexpr int kRing = SHOTKV_SCORE_RING;  // LDS buffers per pair: kRing - 1 blocks in flight
+static_assert(kRing >= 2 && kRing <= 5, "ring depth");
 
 // Issue this wave's share of the direct-to-LDS loads of one 32-key block: groups [g0, g0 + NG).
 // Group i fills rows 4i..4i+3: lane l writes LDS slot l of the group, which is row 4i + l/16, slot
@@ -67,8 +74,13 @@ __device__ __forceinline__ void issue_block(const char* __restrict__ k_plane, in
 }
 
 // Fold the 16 logits a lane holds for one query (key rows 8*(v/4) + 4*half + v%4 of the block) into
-// that query's running (max, sum) in the log2 domain.
-template <bool MASKED>
+// that query's running (reference, sum) in the log2 domain: sum = sum_k 2^(z_k - reference).
+//
+// EXACT: the reference is raised to the block's maximum first (the usual online softmax).  Otherwise the
+// reference found so far is kept and the exponentials are summed against it directly - any reference
+// gives the same softmax once the chunks are combined, and one that is merely an earlier maximum is
+// safe unless a later logit exceeds it by ~2^100; that case is caught on the sum and redone exactly.
+template <bool MASKED, bool EXACT>
 __device__ __forceinline__ void softmax_fold(floatx16 acc, float c, int half, int rem, int key0,
                                              int last_visible, float& m_run, float& l_run) {
   if (MASKED) {
@@ -78,6 +90,20 @@ __device__ __forceinline__ void softmax_fold(floatx16 acc, float c, int half, in
 #pragma unroll
     for (int v = 0; v < 16; ++v)
       if (8 * (v >> 2) + (v & 3) >= limit) acc[v] = -INFINITY;
+  }
+  if (!EXACT) {
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; v += 2) {
+      s0 += __builtin_amdgcn_exp2f(fmaf(acc[v], c, -m_run));
+      s1 += __builtin_amdgcn_exp2f(fmaf(acc[v + 1], c, -m_run));
+    }
+    const float s = s0 + s1;
+    // wave-uniform decision, so the exact path below is taken by all lanes or none
+    if (__builtin_amdgcn_ballot_w64(!(s < 0x1p100f)) == 0) {
+      l_run += s;
+      return;
+    }
   }
   float bm = fmaxf(acc[0], acc[1]);
 #pragma unroll
@@ -96,7 +122,7 @@ __device__ __forceinline__ void softmax_fold(floatx16 acc, float c, int half, in
 }
 
 // One 32-key block against this wave's NQW query blocks (qb0 = index of its first one).
-template <int NQW, bool MASKED>
+template <int NQW, bool MASKED, bool EXACT>
 __device__ __forceinline__ void compute_block(lds_cchar* lds_buf, const bf16x8 (&bq)[NQW][8], int lane,
                                               int qb0, int key0, int rem, int causal_base, int W, float c,
                                               float (&m_run)[NQW], float (&l_run)[NQW]) {
@@ -119,7 +145,7 @@ __device__ __forceinline__ void compute_block(lds_cchar* lds_buf, const bf16x8 (
 #pragma unroll
   for (int q = 0; q < NQW; ++q) {
     const int last_visible = causal_base + ((qb0 + q) * 32 + row) % W;
-    softmax_fold<MASKED>(acc[q], c, half, rem, key0, last_visible, m_run[q], l_run[q]);
+    softmax_fold<MASKED, EXACT>(acc[q], c, half, rem, key0, last_visible, m_run[q], l_run[q]);
   }
 }
 
@@ -129,7 +155,7 @@ struct PairShape {
   static constexpr int kNQW = NQB / kWaves;           // query blocks per wave
   static constexpr int kLoads = kGroupsPerBlock / kWaves;  // load instructions per wave per block
   static constexpr int kThreads = kWaves * kWave;
-  static constexpr int kMinWavesPerSimd = kWaves > 1 ? 3 : 1;  // single-wave groups are LDS-limited
+  static constexpr int kMinWavesPerSimd = kWaves > 1 ? SHOTKV_SCORE_WAVES_PER_SIMD : 1;  // single-wave groups are LDS-limited
 };
 
 template <int NQB>
@@ -201,13 +227,15 @@ score_partials_mfma_kernel(
     pend_c = -1;
   };
 
-  // Stream of 32-key blocks over the workgroup's chunks.  `cur` sits in ring slot cur_buf, `nxt` in
-  // the slot after it, and the block after that is requested as soon as the slot before cur is free.
+  // Stream of 32-key blocks over the workgroup's chunks.  `cur` sits in ring slot cur_buf; up to
+  // kLook = kRing - 1 requested blocks follow it in the next slots (queue q_*[0..n_q)).  A new block is
+  // requested each iteration, right after the barrier that frees the slot of the block before cur.
   // The table entry of the chunk after the newest requested one is fetched a chunk ahead.
+  constexpr int kLook = kRing - 1;
   int tab_c = c_begin + 1;  // next chunk, whose table entry is already on its way
   int tab_key0 = 0, tab_len = 0;
   if (tab_c < c_end) { tab_key0 = cs[tab_c]; tab_len = cl[tab_c]; }
-  int new_c = c_begin, new_key0 = cs[c_begin], new_rem = cl[c_begin];  // newest requested block
+  int new_c = c_begin, new_key0 = cs[c_begin], new_rem = cl[c_begin];  // next block to request
   bool new_valid = true;
   auto advance = [&]() {  // step (new_*) to its successor block
     if (new_rem > kBlockKeys) {
@@ -222,40 +250,58 @@ score_partials_mfma_kernel(
       if (tab_c < c_end) { tab_key0 = cs[tab_c]; tab_len = cl[tab_c]; }
     }
   };
+  auto ring_slot = [](int s) { return s >= kRing ? s - kRing : s; };
 
   int cur_c = new_c, cur_key0 = new_key0, cur_rem = new_rem;
   issue_block<S::kLoads>(k_plane, new_key0, new_rem, lds_addr, g0, lane);
   advance();
-  int nxt_c = new_c, nxt_key0 = new_key0, nxt_rem = new_rem;
-  bool nxt_valid = new_valid;
-  if (nxt_valid) {
-    issue_block<S::kLoads>(k_plane, new_key0, new_rem, lds_addr + kBufBytes, g0, lane);
-    advance();
+  int q_c[kLook], q_key0[kLook], q_rem[kLook];  // indexed with compile-time indices only
+  int n_q = 0;
+#pragma unroll
+  for (int i = 0; i < kLook; ++i) { q_c[i] = 0; q_key0[i] = 0; q_rem[i] = 0; }
+#pragma unroll
+  for (int i = 0; i < kLook - 1; ++i) {
+    if (new_valid) {
+      q_c[i] = new_c; q_key0[i] = new_key0; q_rem[i] = new_rem;
+      issue_block<S::kLoads>(k_plane, new_key0, new_rem, lds_addr + (i + 1) * kBufBytes, g0, lane);
+      n_q = i + 1;
+      advance();
+    }
   }
   int cur_buf = 0;
+  bool first_of_chunk = true;
 
   while (true) {
-    // this wave's share of `cur` has landed once at most the loads of `nxt` are outstanding ...
-    if (nxt_valid) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(S::kLoads) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // this wave's share of `cur` has landed once only the loads of the queued blocks are outstanding
+    if (n_q == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (n_q == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(S::kLoads) : "memory");
+    else if (n_q == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * S::kLoads) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * S::kLoads) : "memory");
     // ... and after the barrier so has the partner's; the pair is also done reading the block before
     if (S::kWaves > 1) asm volatile("s_barrier" ::: "memory");
     if (pend_c >= 0) flush();
-    const bool req_valid = nxt_valid && new_valid;
-    if (req_valid) {
-      int slot = cur_buf + 2;
-      if (slot >= kRing) slot -= kRing;
-      issue_block<S::kLoads>(k_plane, new_key0, new_rem, lds_addr + slot * kBufBytes, g0, lane);
+    if (new_valid) {
+#pragma unroll
+      for (int i = 0; i < kLook; ++i)
+        if (i == n_q) { q_c[i] = new_c; q_key0[i] = new_key0; q_rem[i] = new_rem; }
+      issue_block<S::kLoads>(k_plane, new_key0, new_rem, lds_addr + ring_slot(cur_buf + n_q + 1) * kBufBytes,
+                             g0, lane);
+      ++n_q;
+      advance();
     }
     // keys past the end of the chunk and keys a window query may not see yet are masked; both only
     // happen in a chunk's last block or in the last W keys, so the common block takes the plain path
     const bool masked = cur_rem < kBlockKeys || cur_key0 + kBlockKeys - 1 > causal_base;
+    // a chunk's first block (no reference yet) and masked blocks (a lane may have seen nothing but
+    // masked keys so far) take the exact online-softmax update, the rest the cheaper one
+    lds_cchar* blk = lds_base + cur_buf * kBufBytes;
     if (masked)
-      compute_block<NQW, true>(lds_base + cur_buf * kBufBytes, bq, lane, qb0, cur_key0, cur_rem, causal_base,
-                               W, c, m_run, l_run);
+      compute_block<NQW, true, true>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
+    else if (first_of_chunk)
+      compute_block<NQW, false, true>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
     else
-      compute_block<NQW, false>(lds_base + cur_buf * kBufBytes, bq, lane, qb0, cur_key0, cur_rem,
-                                causal_base, W, c, m_run, l_run);
+      compute_block<NQW, false, false>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
+    first_of_chunk = false;
 
     if (cur_rem <= kBlockKeys) {  // last block of its chunk: merge the lane halves
 #pragma unroll
@@ -270,13 +316,14 @@ score_partials_mfma_kernel(
         l_run[q] = 0.f;
       }
       pend_c = cur_c;
+      first_of_chunk = true;
     }
-    if (!nxt_valid) break;
-    cur_c = nxt_c; cur_key0 = nxt_key0; cur_rem = nxt_rem;
-    nxt_valid = req_valid;
-    nxt_c = new_c; nxt_key0 = new_key0; nxt_rem = new_rem;
-    if (req_valid) advance();
-    cur_buf = cur_buf + 1 == kRing ? 0 : cur_buf + 1;
+    if (n_q == 0) break;
+    cur_c = q_c[0]; cur_key0 = q_key0[0]; cur_rem = q_rem[0];
+#pragma unroll
+    for (int i = 0; i + 1 < kLook; ++i) { q_c[i] = q_c[i + 1]; q_key0[i] = q_key0[i + 1]; q_rem[i] = q_rem[i + 1]; }
+    --n_q;
+    cur_buf = ring_slot(cur_buf + 1);
   }
   if (pend_c >= 0) flush();
 }

@@ -238,3 +238,26 @@ def test_host_side_errors(kv):
         ws = torch.empty(kv.prefill_workspace_bytes(8, 2, 128, 32, torch.bfloat16, 1, 100, 1) + 16,
                          dtype=torch.uint8, device="cuda")
         kv.prefill_compress(q, k, k, off, bud, 64, 0.1, workspace=ws[8:])
+
+
+def test_logits_far_above_the_running_reference(kv):
+    """Inside one shot the first 32 keys are small and a later block holds keys whose logits exceed the
+    reference found so far by more than 2^100: the score kernel must fall back to the exact online
+    update there (and must not overflow)."""
+    H, Hkv, D, W, N = 32, 8, 128, 32, 1024
+    g = torch.Generator(device="cuda").manual_seed(21)
+    u = torch.zeros(D, device="cuda"); u[:4] = 0.5                       # unit vector
+    q = (4.0 * u).expand(1, H, W, D).contiguous().to(torch.bfloat16)
+    k = (0.01 * torch.randn((1, Hkv, N, D), generator=g, device="cuda")).to(torch.bfloat16)
+    k[:, :, 300:340, :] = (30.0 * u).to(torch.bfloat16)                   # logits 120 with sm_scale 1
+    k[:, :, 700:705, :] = (31.0 * u).to(torch.bfloat16)                   # and a still larger, later group
+    v = torch.zeros_like(k)
+    off = torch.tensor([[0, 256, 512, 768, 960]], dtype=torch.int32, device="cuda")
+    scores, status = kv.prefill_scores(q, k, off, 1.0)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0]
+    ref = oracle_prefill(q[0], k[0], v[0], off[0].cpu().numpy(), N, 1.0)
+    got = scores[0].cpu().numpy()
+    assert np.all(np.isfinite(got))
+    np.testing.assert_allclose(got, ref["scores"], rtol=1e-3, atol=1e-30)
+    assert got[2] > 1.0 and got[0] < 1e-20                                 # the mass sits in shot 2
