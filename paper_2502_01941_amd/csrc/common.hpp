@@ -172,6 +172,10 @@ inline DecodeWorkspace carve_decode(void* base, int S, int H, int H_kv, int D, i
 }
 
 int decode_splits(int S, int H_kv, int total_tokens);
+bool decode_uses_mfma(const DecodeDims& d);
+hipError_t launch_decode_partial_mfma(const DecodeDims& d, const shotkv_decode_state& st, const void* q_new,
+                                      const void* k_new, const void* v_new, const DecodeWorkspace& w,
+                                      hipStream_t s);
 
 hipError_t launch_decode_partial(const DecodeDims& d, const shotkv_decode_state& st, const void* q_new,
                                  const void* k_new, const void* v_new, const DecodeWorkspace& w,

@@ -279,26 +279,27 @@ __global__ __launch_bounds__(kFinThreads) void decode_merge_kernel(
     return;
   }
 
-  // global softmax statistics of this group's heads: one wave per head, lanes over the splits
+  // global softmax statistics of this group's heads: one wave per head, lanes over the splits; each
+  // split's weight 2^(m - M) is kept so that the merge below is a plain weighted sum of loads that do
+  // not depend on one another
+  __shared__ float s_w[8][kWave];
   for (int hl = wave; hl < G; hl += kFinWaves) {
     const float2* ml = part_ml + (head0 + hl) * n_splits;
     float m = -INFINITY, l = 0.f;
     if (lane < n_splits) { const float2 x = ml[lane]; m = x.x; l = x.y; }
     const float M = wave_max(m);
-    const float L = wave_sum(l > 0.f ? l * __builtin_amdgcn_exp2f(m - M) : 0.f);
+    const float wgt = l > 0.f ? __builtin_amdgcn_exp2f(m - M) : 0.f;
+    const float L = wave_sum(l * wgt);
+    s_w[hl][lane] = wgt;
     if (lane == 0) { s_M[hl] = M; s_invL[hl] = 1.f / L; }
   }
   __syncthreads();
 
   for (int idx = tid; idx < G * D; idx += kFinThreads) {
     const int hl = idx / D, dd = idx % D;
-    const float2* ml = part_ml + (head0 + hl) * n_splits;
     const float* po = part_o + (head0 + hl) * n_splits * D + dd;
     float acc = 0.f;
-    for (int i = 0; i < n_splits; ++i) {
-      const float2 x = ml[i];
-      if (x.y > 0.f) acc += po[static_cast<size_t>(i) * D] * __builtin_amdgcn_exp2f(x.x - s_M[hl]);
-    }
+    for (int i = 0; i < n_splits; ++i) acc = fmaf(po[static_cast<size_t>(i) * D], s_w[hl][i], acc);
     out[(head0 + hl) * D + dd] = acc * s_invL[hl];
   }
 
@@ -395,6 +396,8 @@ int decode_splits(int S, int H_kv, int total_tokens) {
   int splits = ceil_div(SHOTKV_DEC_TARGET_GROUPS, pairs);
   const int max_by_tokens = total_tokens / 128 > 0 ? total_tokens / 128 : 1;
   if (splits > max_by_tokens) splits = max_by_tokens;
+  const int min_by_range = ceil_div(total_tokens, 1024);  // the matrix-core path holds <= 1024 logits
+  if (splits < min_by_range) splits = min_by_range;
   if (splits > kWave) splits = kWave;
   if (splits < 1) splits = 1;
   return splits;
@@ -428,6 +431,7 @@ static hipError_t launch_partial_g(const DecodeDims& d, const shotkv_decode_stat
 hipError_t launch_decode_partial(const DecodeDims& d, const shotkv_decode_state& st, const void* q_new,
                                  const void* k_new, const void* v_new, const DecodeWorkspace& w,
                                  hipStream_t s) {
+  if (decode_uses_mfma(d)) return launch_decode_partial_mfma(d, st, q_new, k_new, v_new, w, s);
   if (d.dtype == SHOTKV_BF16) {
     if (d.D == 128) return launch_partial_g<bf16_t, 128>(d, st, q_new, k_new, v_new, w, s);
     if (d.D == 64) return launch_partial_g<bf16_t, 64>(d, st, q_new, k_new, v_new, w, s);

@@ -1,0 +1,273 @@
+// Split-KV decode attention for bf16, head_dim 128, with the logits on the matrix cores
+// (Section 5.1, Eq. 7 and 9: attention of the current query over prefill rows and decode slots).
+//
+// A workgroup owns one token range of one (sequence, KV head) and makes two passes over it:
+//   1. K pass: S^T[32 tokens x heads] = K_blk * Q^T with v_mfma_f32_32x32x16_bf16 (the G query heads of
+//      the group sit in the first G columns, the rest are zero); each lane fetches its token row's
+//      A operands straight from global memory (8 x 16 bytes).  The scaled logits go to LDS.
+//   between: validity mask (free slots), per-head maximum, weights 2^(z - max) and their sums, all on
+//      the logits in LDS; decode-slot logits are also written out for the retention score (Eq. 7).
+//   2. V pass: 16 lanes stream one V row each (16 bytes per lane) and accumulate weight * V with the
+//      weights read from LDS.  No rescaling is needed because the maximum is already known.
+// Compared with a one-pass online softmax this moves the dot products off the vector ALU, removes the
+// cross-lane reductions per token and the per-token rescale of the output accumulators.
+#include "common.hpp"
+
+namespace shotkv {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float floatx16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kD = 128;
+constexpr int kMaxRange = 1024;  // tokens per workgroup the LDS logit buffer can hold
+
+// lowest free slot of a sequence, -1 if none; every thread of the block gets the answer
+__device__ int lowest_free_slot(const int32_t* __restrict__ slot_pos, int n_slots, int* s_red) {
+  int best = INT32_MAX;
+  for (int i = threadIdx.x; i < n_slots; i += blockDim.x)
+    if (slot_pos[i] < 0) { best = i; break; }
+  for (int o = kWave / 2; o > 0; o >>= 1) best = min(best, __shfl_xor(best, o, kWave));
+  if (threadIdx.x % kWave == 0) s_red[threadIdx.x / kWave] = best;
+  __syncthreads();
+  int r = INT32_MAX;
+  for (int w = 0; w < kWaves; ++w) r = min(r, s_red[w]);
+  __syncthreads();
+  return r == INT32_MAX ? -1 : r;
+}
+
+template <int G>
+__global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
+    const bf16_t* __restrict__ k_prefill, const bf16_t* __restrict__ v_prefill,
+    const int32_t* __restrict__ prefill_count, bf16_t* __restrict__ k_dec, bf16_t* __restrict__ v_dec,
+    const int32_t* __restrict__ slot_pos, int cap, int n_slots, int H, int H_kv, int n_splits,
+    int split_tokens, float scale_log2e, const bf16_t* __restrict__ q_new,
+    const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new, float2* __restrict__ part_ml,
+    float* __restrict__ part_o, float* __restrict__ z_dec, int32_t* __restrict__ new_slot_out) {
+  const int split = blockIdx.x, g = blockIdx.y, s = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+
+  __shared__ __attribute__((aligned(16))) float zbuf[kMaxRange][G];  // logits, then weights
+  __shared__ float s_part[kWaves][G];
+  __shared__ float s_M[G];
+  __shared__ float s_L[G];
+  __shared__ float s_o[kWaves][G][kD];
+  __shared__ int s_red[kWaves];
+
+  const int32_t* sp = slot_pos + static_cast<size_t>(s) * n_slots;
+  const int pc = min(prefill_count[s], cap);
+  const int t_begin = split * split_tokens;
+  const int t_end = min(t_begin + split_tokens, pc + n_slots);
+  const int T = max(t_end - t_begin, 0);
+  // only a range that reaches into the decode slots needs to know which slot takes the new token
+  const int new_slot = (t_end > pc) ? lowest_free_slot(sp, n_slots, s_red) : n_slots;
+  if (t_end > pc && t_end == pc + n_slots && g == 0 && tid == 0) new_slot_out[s] = new_slot;
+
+  const size_t plane_p = (static_cast<size_t>(s) * H_kv + g) * cap;
+  const size_t plane_d = (static_cast<size_t>(s) * H_kv + g) * n_slots;
+  const size_t new_off = (static_cast<size_t>(s) * H_kv + g) * kD;
+  const size_t head0 = static_cast<size_t>(s) * H + static_cast<size_t>(g) * G;
+
+  // token t of the sequence: live prefill row, occupied slot, the slot taking the new token, or nothing
+  auto token_valid = [&](int t) {
+    if (t < pc) return true;
+    const int slot = t - pc;
+    return slot < n_slots && (slot == new_slot || sp[slot] >= 0);
+  };
+
+  if (new_slot >= 0 && T > 0) {
+    // ---- pass 1: logits ------------------------------------------------------------------------
+    const int row = lane & 31, half = lane >> 5;
+    bf16x8 bq[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      u32x4 raw = {0u, 0u, 0u, 0u};
+      if (row < G)
+        raw = *reinterpret_cast<const u32x4*>(q_new + (head0 + row) * kD + ks * 16 + half * 8);
+      bq[ks] = __builtin_bit_cast(bf16x8, raw);
+    }
+    for (int blk = wave; blk * 32 < T; blk += kWaves) {
+      const int tt = blk * 32 + row;
+      const int t = t_begin + tt;
+      // rows past the range and free slots read the new token's key instead (always valid memory);
+      // their logits are masked between the passes
+      const bf16_t* kr = k_new + new_off;
+      bool is_new = false;
+      if (tt < T) {
+        if (t < pc) {
+          kr = k_prefill + (plane_p + t) * kD;
+        } else {
+          const int slot = t - pc;
+          is_new = slot == new_slot;
+          if (!is_new && sp[slot] >= 0) kr = k_dec + (plane_d + slot) * kD;
+        }
+      }
+      u32x4 raw[8];
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) raw[ks] = *reinterpret_cast<const u32x4*>(kr + (2 * ks + half) * 8);
+      if (is_new) {  // append: only this workgroup reads the slot this step
+        bf16_t* dst = k_dec + (plane_d + new_slot) * kD;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) *reinterpret_cast<u32x4*>(dst + (2 * ks + half) * 8) = raw[ks];
+      }
+      floatx16 acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw[ks]), bq[ks], acc, 0, 0, 0);
+      // accumulator v of lane (row, half): token 8*(v/4) + 4*half + v%4 of the block, head `row`
+      if (row < G) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = blk * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+          if (m < T) zbuf[m][row] = acc[v] * scale_log2e;
+        }
+      }
+    }
+    __syncthreads();
+
+    // ---- between the passes: mask, maximum, weights, sums (thread tid always sees head tid % G) --
+    const int h = tid % G;
+    float mx = -INFINITY;
+    for (int idx = tid; idx < T * G; idx += kThreads) {
+      const int tt = idx / G;
+      float z = zbuf[tt][h];
+      if (!token_valid(t_begin + tt)) { z = -INFINITY; zbuf[tt][h] = z; }
+      mx = fmaxf(mx, z);
+    }
+#pragma unroll
+    for (int o = G; o < kWave; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, kWave));
+    if (lane < G) s_part[wave][lane] = mx;
+    __syncthreads();
+    if (tid < G) {
+      float m = s_part[0][tid];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) m = fmaxf(m, s_part[w][tid]);
+      s_M[tid] = m;
+    }
+    __syncthreads();
+    const float M = s_M[h];
+    float sum = 0.f;
+    for (int idx = tid; idx < T * G; idx += kThreads) {
+      const int tt = idx / G;
+      const float z = zbuf[tt][h];
+      const int t = t_begin + tt;
+      if (t >= pc && z != -INFINITY) z_dec[(head0 + h) * n_slots + (t - pc)] = z;
+      const float p = (z == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(z - M);
+      zbuf[tt][h] = p;
+      sum += p;
+    }
+#pragma unroll
+    for (int o = G; o < kWave; o <<= 1) sum += __shfl_xor(sum, o, kWave);
+    __syncthreads();  // s_part is reused
+    if (lane < G) s_part[wave][lane] = sum;
+    __syncthreads();
+    if (tid < G) {
+      float l = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) l += s_part[w][tid];
+      s_L[tid] = l;
+    }
+    __syncthreads();
+  } else {
+    if (tid < G) { s_M[tid] = -INFINITY; s_L[tid] = 0.f; }
+    __syncthreads();
+  }
+
+  // ---- pass 2: weighted values -------------------------------------------------------------------
+  constexpr int kGroups = kThreads / 16;  // 16 lanes per V row
+  const int grp = tid >> 4, lir = tid & 15;
+  float o[G][8];
+#pragma unroll
+  for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[hh][e] = 0.f;
+  if (new_slot >= 0) {
+    for (int tt = grp; tt < T; tt += kGroups) {
+      float p[G];
+      bool any = false;
+#pragma unroll
+      for (int hh = 0; hh < G; ++hh) { p[hh] = zbuf[tt][hh]; any = any || p[hh] != 0.f; }
+      if (!any) continue;  // masked token, or weights that underflowed to exactly zero
+      const int t = t_begin + tt;
+      const bf16_t* vr;
+      const bool is_new = t >= pc && (t - pc) == new_slot;
+      if (t < pc) vr = v_prefill + (plane_p + t) * kD;
+      else if (is_new) vr = v_new + new_off;
+      else vr = v_dec + (plane_d + (t - pc)) * kD;
+      const u32x4 raw = *reinterpret_cast<const u32x4*>(vr + lir * 8);
+      if (is_new) *reinterpret_cast<u32x4*>(v_dec + (plane_d + new_slot) * kD + lir * 8) = raw;
+      float vf[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        vf[2 * i] = __uint_as_float(raw[i] << 16);
+        vf[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+      }
+#pragma unroll
+      for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[hh][e] = fmaf(p[hh], vf[e], o[hh][e]);
+    }
+  }
+  // sum over the four row groups of a wave, then over the waves
+#pragma unroll
+  for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      o[hh][e] += __shfl_xor(o[hh][e], 16, kWave);
+      o[hh][e] += __shfl_xor(o[hh][e], 32, kWave);
+    }
+  if (lane < 16) {
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s_o[wave][hh][lir * 8 + e] = o[hh][e];
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * kD; idx += kThreads) {
+    const int hh = idx / kD, dd = idx % kD;
+    float acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) acc += s_o[w][hh][dd];
+    const size_t r = (head0 + hh) * n_splits + split;
+    part_o[r * kD + dd] = acc;
+    if (dd == 0) part_ml[r] = make_float2(s_M[hh], s_L[hh]);
+  }
+}
+
+}  // namespace
+
+bool decode_uses_mfma(const DecodeDims& d) {
+  return d.dtype == SHOTKV_BF16 && d.D == kD && d.split_tokens <= kMaxRange;
+}
+
+hipError_t launch_decode_partial_mfma(const DecodeDims& d, const shotkv_decode_state& st, const void* q_new,
+                                      const void* k_new, const void* v_new, const DecodeWorkspace& w,
+                                      hipStream_t s) {
+  const dim3 grid(d.n_splits, d.H_kv, d.S), block(kThreads);
+  const float c = d.sm_scale * kLog2e;
+  KernelTimer timer(kKernelDecodePartial, s);
+#define SHOTKV_LAUNCH_DEC(GG)                                                                           \
+  hipLaunchKernelGGL(decode_partial_mfma_kernel<GG>, grid, block, 0, s,                                 \
+                     static_cast<const bf16_t*>(st.k_prefill), static_cast<const bf16_t*>(st.v_prefill), \
+                     st.prefill_count, static_cast<bf16_t*>(st.k_dec), static_cast<bf16_t*>(st.v_dec),   \
+                     st.slot_pos, d.cap, d.n_slots, d.H, d.H_kv, d.n_splits, d.split_tokens, c,          \
+                     static_cast<const bf16_t*>(q_new), static_cast<const bf16_t*>(k_new),               \
+                     static_cast<const bf16_t*>(v_new), w.part_ml, w.part_o, w.z_dec, w.new_slot)
+  switch (d.G) {
+    case 1: SHOTKV_LAUNCH_DEC(1); break;
+    case 2: SHOTKV_LAUNCH_DEC(2); break;
+    case 4: SHOTKV_LAUNCH_DEC(4); break;
+    case 8: SHOTKV_LAUNCH_DEC(8); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef SHOTKV_LAUNCH_DEC
+  return hipGetLastError();
+}
+
+}  // namespace shotkv
