@@ -74,9 +74,10 @@ struct PrefillWorkspace {
   int32_t* chunk_len;     // [P][maxC] keys in the chunk (<= chunk_keys)
   int32_t* seg_first;     // [P][n_shots+3] first chunk of segment s; segment 0 = prefix, 1..n = shots,
                           //                n+1 = tail, entry n+2 = n_chunks
-  // softmax partials per (problem, kv head, chunk, row): running max (log2 domain) and sum
-  float2*  partial;       // [P][H_kv][maxC][R]
-  float2*  row_stat;      // [P][H_kv][R]  (global max, 1 / global sum)
+  // softmax partial per (problem, kv head, chunk, row): log2 of the chunk's sum of exponentials
+  // (-inf for a row that sees none of the chunk's keys)
+  float*   partial;       // [P][H_kv][maxC][R]
+  float*   row_stat;      // [P][H_kv][R]  log2 of the row's sum of exponentials over all chunks
   float*   chunk_mass;    // [P][maxC]
   float*   scores;        // [P][n_shots]
   int32_t  max_c;
@@ -103,8 +104,8 @@ inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_
   w.chunk_start = reinterpret_cast<int32_t*>(take(P_ * C * 4));
   w.chunk_len = reinterpret_cast<int32_t*>(take(P_ * C * 4));
   w.seg_first = reinterpret_cast<int32_t*>(take(P_ * (S + 3) * 4));
-  w.partial = reinterpret_cast<float2*>(take(P_ * H_kv * C * R * 8));
-  w.row_stat = reinterpret_cast<float2*>(take(P_ * H_kv * R * 8));
+  w.partial = reinterpret_cast<float*>(take(P_ * H_kv * C * R * 4));
+  w.row_stat = reinterpret_cast<float*>(take(P_ * H_kv * R * 4));
   w.chunk_mass = reinterpret_cast<float*>(take(P_ * C * 4));
   w.scores = reinterpret_cast<float*>(take(P_ * S * 4 + 4));
   w.bytes = off;

@@ -1,7 +1,7 @@
 // Segmented per-shot reduction of the softmax partials (Section 5.1, Eq. 3).
 //
-//   row_stats   : per (problem, KV head, query row) the global max M and 1/L over all chunks
-//   chunk_mass  : per (problem, chunk) the attention mass sum_{heads, rows} l * 2^(m - M) / L
+//   row_stats   : per (problem, KV head, query row) log2 of the softmax denominator over all chunks
+//   chunk_mass  : per (problem, chunk) the attention mass sum_{heads, rows} 2^(lse_chunk - lse_row)
 //   shot_scores : Score(s_i) = (sum of the masses of the shot's chunks) / k_i
 // All sums are in fixed order (no atomics), so results are reproducible run to run.
 #include "common.hpp"
@@ -12,27 +12,28 @@ namespace {
 
 constexpr int kStatThreads = 1024;
 
-__global__ __launch_bounds__(kStatThreads) void row_stats_kernel(const float2* __restrict__ partial,
+// log2(2^a + 2^b) style accumulation of (max, sum) with a partial given as log2 of a sum
+__device__ __forceinline__ void lse_accumulate(float& M, float& L, float x) {
+  if (x > -INFINITY) {
+    const float Mn = fmaxf(M, x);
+    L = L * exp2f(M - Mn) + exp2f(x - Mn);
+    M = Mn;
+  }
+}
+
+__global__ __launch_bounds__(kStatThreads) void row_stats_kernel(const float* __restrict__ partial,
                                                                  const int32_t* __restrict__ n_chunks,
                                                                  int H_kv, int R, int max_c,
-                                                                 float2* __restrict__ row_stat) {
+                                                                 float* __restrict__ row_stat) {
   const int g = blockIdx.x, p = blockIdx.y;
   const int nl = kStatThreads / R;  // chunk lanes
   const int tid = threadIdx.x;
   const int r = tid % R, cl = tid / R;
   const int nc = n_chunks[p];
-  const float2* base = partial + (static_cast<size_t>(p) * H_kv + g) * max_c * R;
+  const float* base = partial + (static_cast<size_t>(p) * H_kv + g) * max_c * R;
   float M = -INFINITY, L = 0.f;
-  if (cl < nl) {
-    for (int c = cl; c < nc; c += nl) {
-      const float2 ml = base[static_cast<size_t>(c) * R + r];
-      if (ml.y > 0.f) {
-        const float Mn = fmaxf(M, ml.x);
-        L = L * exp2f(M - Mn) + ml.y * exp2f(ml.x - Mn);
-        M = Mn;
-      }
-    }
-  }
+  if (cl < nl)
+    for (int c = cl; c < nc; c += nl) lse_accumulate(M, L, base[static_cast<size_t>(c) * R + r]);
   __shared__ float sM[kStatThreads];
   __shared__ float sL[kStatThreads];
   sM[tid] = M;
@@ -48,15 +49,15 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(const float2* _
         Mt = Mn;
       }
     }
-    row_stat[(static_cast<size_t>(p) * H_kv + g) * R + tid] =
-        make_float2(Mt, Lt > 0.f ? 1.f / Lt : 0.f);
+    // log2 of the row's softmax denominator; +inf for a row without keys so that its weights vanish
+    row_stat[(static_cast<size_t>(p) * H_kv + g) * R + tid] = Lt > 0.f ? Mt + log2f(Lt) : INFINITY;
   }
 }
 
 constexpr int kMassThreads = 256;
 
-__global__ __launch_bounds__(kMassThreads) void chunk_mass_kernel(const float2* __restrict__ partial,
-                                                                  const float2* __restrict__ row_stat,
+__global__ __launch_bounds__(kMassThreads) void chunk_mass_kernel(const float* __restrict__ partial,
+                                                                  const float* __restrict__ row_stat,
                                                                   const int32_t* __restrict__ n_chunks,
                                                                   int H_kv, int R, int max_c,
                                                                   float* __restrict__ chunk_mass) {
@@ -64,15 +65,11 @@ __global__ __launch_bounds__(kMassThreads) void chunk_mass_kernel(const float2* 
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int c = blockIdx.x * (kMassThreads / kWave) + wave;
   if (c >= n_chunks[p]) return;
-  const float2* stat = row_stat + static_cast<size_t>(p) * H_kv * R;
+  const float* stat = row_stat + static_cast<size_t>(p) * H_kv * R;
   float acc = 0.f;
   for (int g = 0; g < H_kv; ++g) {
-    const float2* part = partial + ((static_cast<size_t>(p) * H_kv + g) * max_c + c) * R;
-    for (int r = lane; r < R; r += kWave) {
-      const float2 ml = part[r];
-      const float2 st = stat[g * R + r];
-      if (ml.y > 0.f) acc += ml.y * exp2f(ml.x - st.x) * st.y;
-    }
+    const float* part = partial + ((static_cast<size_t>(p) * H_kv + g) * max_c + c) * R;
+    for (int r = lane; r < R; r += kWave) acc += exp2f(part[r] - stat[g * R + r]);  // 2^-inf = 0
   }
   acc = wave_sum(acc);
   if (lane == 0) chunk_mass[static_cast<size_t>(p) * max_c + c] = acc;

@@ -1,8 +1,8 @@
 // Window-attention softmax partials, shape-generic path (Section 5.1, Eq. 3: alpha_{t,h}).
 //
 // One workgroup takes one chunk of at most 64 keys of one KV head and, for each of the R = G*W query
-// rows attached to that head, produces the chunk-local softmax statistics (max, sum of exponentials)
-// in the log2 domain.  The global normalisation happens in the reduction kernels.  This path serves
+// rows attached to that head, produces the chunk-local softmax statistic log2(sum of exponentials)
+// (logits in the log2 domain).  The global normalisation happens in the reduction kernels.  This path serves
 // fp32 inputs and shapes the matrix-core kernel does not cover; it is plain vector arithmetic.
 #include "common.hpp"
 
@@ -18,7 +18,7 @@ __global__ __launch_bounds__(kThreads) void score_partials_generic_kernel(
     const T* __restrict__ q_obs, const T* __restrict__ k, int n_tokens, int H, int H_kv, int G, int D,
     int W, float scale_log2e, const int32_t* __restrict__ n_chunks,
     const int32_t* __restrict__ chunk_start, const int32_t* __restrict__ chunk_len, int max_c,
-    float2* __restrict__ partial) {
+    float* __restrict__ partial) {
   const int c = blockIdx.x, g = blockIdx.y, p = blockIdx.z;
   if (c >= n_chunks[p]) return;
   const int start = chunk_start[static_cast<size_t>(p) * max_c + c];
@@ -35,7 +35,7 @@ __global__ __launch_bounds__(kThreads) void score_partials_generic_kernel(
   __syncthreads();
 
   const T* qbase = q_obs + (static_cast<size_t>(p) * H + static_cast<size_t>(g) * G) * W * D;
-  float2* out = partial + ((static_cast<size_t>(p) * H_kv + g) * max_c + c) * R;
+  float* out = partial + ((static_cast<size_t>(p) * H_kv + g) * max_c + c) * R;
   for (int r = wave; r < R; r += kThreads / kWave) {
     const int j = r % W;
     const int last_visible = n_tokens - W + j;  // the query's own position
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kThreads) void score_partials_generic_kernel(
     const float m = wave_max(z);
     const float e = (z == -INFINITY) ? 0.f : exp2f(z - m);
     const float l = wave_sum(e);
-    if (lane == 0) out[r] = make_float2(m, (m == -INFINITY) ? 0.f : l);
+    if (lane == 0) out[r] = (m == -INFINITY) ? -INFINITY : m + log2f(l);  // log2 sum_k 2^z_k
   }
 }
 

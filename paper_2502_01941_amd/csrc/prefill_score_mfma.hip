@@ -164,7 +164,7 @@ score_partials_mfma_kernel(
     const bf16_t* __restrict__ q_obs, const bf16_t* __restrict__ k, int n_tokens, int H, int H_kv, int W,
     float c, const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ chunk_start,
     const int32_t* __restrict__ chunk_len, int max_c, int chunks_per_group,
-    float2* __restrict__ partial) {
+    float* __restrict__ partial) {
   typedef PairShape<NQB> S;
   constexpr int NQW = S::kNQW;
   constexpr int R = NQB * 32;
@@ -184,7 +184,7 @@ score_partials_mfma_kernel(
       reinterpret_cast<const char*>(k) + (static_cast<size_t>(p) * H_kv + g) * n_tokens * kRowBytes;
   const int G = H / H_kv;
   const bf16_t* q_rows = q_obs + (static_cast<size_t>(p) * H + static_cast<size_t>(g) * G) * W * kD;
-  float2* out = partial + (static_cast<size_t>(p) * H_kv + g) * max_c * R;
+  float* out = partial + (static_cast<size_t>(p) * H_kv + g) * max_c * R;
   const int qb0 = wave * NQW;
 
   // B operands: query row (qb0+q)*32 + lane%32, head-dim slice 16*ks + 8*(lane/32) .. +8
@@ -211,18 +211,16 @@ score_partials_mfma_kernel(
 #pragma unroll
   for (int q = 0; q < NQW; ++q) { m_run[q] = -INFINITY; l_run[q] = 0.f; }
 
-  // A finished chunk's statistics are stored one block later, ahead of that iteration's loads: the
+  // A finished chunk's statistic, log2(sum_k 2^z_k) per query, is stored one block later, ahead of that iteration's loads: the
   // wait that follows a store also covers it, so it gets a whole block of compute to complete.  Row
   // r of the partial array is query (lane%32)*NQB + qb; lanes 0..31 store this wave's query blocks.
-  float2 pend[NQW];
+  float pend[NQW];  // log2 of the chunk's sum of exponentials per query
   int pend_c = -1;
   auto flush = [&]() {
-    float2* dst = out + static_cast<size_t>(pend_c) * R + (lane & 31) * NQB + qb0;
+    float* dst = out + static_cast<size_t>(pend_c) * R + (lane & 31) * NQB + qb0;
     if (lane < 32) {
-      if (NQW == 2)
-        *reinterpret_cast<float4*>(dst) = make_float4(pend[0].x, pend[0].y, pend[NQW - 1].x, pend[NQW - 1].y);
-      else
-        dst[0] = pend[0];
+      if (NQW == 2) *reinterpret_cast<float2*>(dst) = make_float2(pend[0], pend[NQW - 1]);
+      else dst[0] = pend[0];
     }
     pend_c = -1;
   };
@@ -310,8 +308,9 @@ score_partials_mfma_kernel(
         const float lo = __shfl_xor(l_run[q], 32, kWave);
         const float mn = fmaxf(m_run[q], mo);
         const float ms = (mn == -INFINITY) ? 0.f : mn;
-        pend[q] = make_float2(mn, l_run[q] * __builtin_amdgcn_exp2f(m_run[q] - ms) +
-                                      lo * __builtin_amdgcn_exp2f(mo - ms));
+        const float l = l_run[q] * __builtin_amdgcn_exp2f(m_run[q] - ms) + lo * __builtin_amdgcn_exp2f(mo - ms);
+        // a + b is the same in both halves, so lanes l and l+32 hold identical results; log2(0) = -inf
+        pend[q] = mn + __builtin_amdgcn_logf(l);
         m_run[q] = -INFINITY;
         l_run[q] = 0.f;
       }
