@@ -25,6 +25,10 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kD = 128;
 constexpr int kMaxRange = 1024;  // tokens per workgroup the LDS logit buffer can hold
+#ifndef SHOTKV_DEC_V_UNROLL
+#define SHOTKV_DEC_V_UNROLL 2
+#endif
+constexpr int kVUnroll = SHOTKV_DEC_V_UNROLL;  // V rows a lane group has in flight
 
 // lowest free slot of a sequence, -1 if none; every thread of the block gets the answer
 __device__ int lowest_free_slot(const int32_t* __restrict__ slot_pos, int n_slots, int* s_red) {
@@ -188,30 +192,46 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[hh][e] = 0.f;
   if (new_slot >= 0) {
-    for (int tt = grp; tt < T; tt += kGroups) {
-      float p[G];
-      bool any = false;
+    // kVUnroll rows per lane group are requested before any of them is used
+    for (int tt0 = grp; tt0 < T; tt0 += kGroups * kVUnroll) {
+      float p[kVUnroll][G];
+      u32x4 raw[kVUnroll];
+      bool use[kVUnroll];
 #pragma unroll
-      for (int hh = 0; hh < G; ++hh) { p[hh] = zbuf[tt][hh]; any = any || p[hh] != 0.f; }
-      if (!any) continue;  // masked token, or weights that underflowed to exactly zero
-      const int t = t_begin + tt;
-      const bf16_t* vr;
-      const bool is_new = t >= pc && (t - pc) == new_slot;
-      if (t < pc) vr = v_prefill + (plane_p + t) * kD;
-      else if (is_new) vr = v_new + new_off;
-      else vr = v_dec + (plane_d + (t - pc)) * kD;
-      const u32x4 raw = *reinterpret_cast<const u32x4*>(vr + lir * 8);
-      if (is_new) *reinterpret_cast<u32x4*>(v_dec + (plane_d + new_slot) * kD + lir * 8) = raw;
-      float vf[8];
+      for (int u = 0; u < kVUnroll; ++u) {
+        const int tt = tt0 + u * kGroups;
+        use[u] = false;
+        if (tt < T) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        vf[2 * i] = __uint_as_float(raw[i] << 16);
-        vf[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+          for (int hh = 0; hh < G; ++hh) { p[u][hh] = zbuf[tt][hh]; use[u] = use[u] || p[u][hh] != 0.f; }
+        }
+        // a masked token, or weights that underflowed to exactly zero, contribute nothing
+        if (use[u]) {
+          const int t = t_begin + tt;
+          const bf16_t* vr;
+          const bool is_new = t >= pc && (t - pc) == new_slot;
+          if (t < pc) vr = v_prefill + (plane_p + t) * kD;
+          else if (is_new) vr = v_new + new_off;
+          else vr = v_dec + (plane_d + (t - pc)) * kD;
+          raw[u] = *reinterpret_cast<const u32x4*>(vr + lir * 8);
+          if (is_new) *reinterpret_cast<u32x4*>(v_dec + (plane_d + new_slot) * kD + lir * 8) = raw[u];
+        }
       }
 #pragma unroll
-      for (int hh = 0; hh < G; ++hh)
+      for (int u = 0; u < kVUnroll; ++u) {
+        if (use[u]) {
+          float vf[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[hh][e] = fmaf(p[hh], vf[e], o[hh][e]);
+          for (int i = 0; i < 4; ++i) {
+            vf[2 * i] = __uint_as_float(raw[u][i] << 16);
+            vf[2 * i + 1] = __uint_as_float(raw[u][i] & 0xffff0000u);
+          }
+#pragma unroll
+          for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[hh][e] = fmaf(p[u][hh], vf[e], o[hh][e]);
+        }
+      }
     }
   }
   // sum over the four row groups of a wave, then over the waves

@@ -151,7 +151,10 @@ __device__ __forceinline__ void compute_block(lds_cchar* lds_buf, const bf16x8 (
 
 template <int NQB>
 struct PairShape {
-  static constexpr int kWaves = NQB >= 2 ? 2 : 1;     // waves per workgroup
+#ifndef SHOTKV_SCORE_MAX_WAVES
+#define SHOTKV_SCORE_MAX_WAVES 2
+#endif
+  static constexpr int kWaves = NQB >= SHOTKV_SCORE_MAX_WAVES ? SHOTKV_SCORE_MAX_WAVES : (NQB >= 2 ? 2 : 1);  // waves per workgroup
   static constexpr int kNQW = NQB / kWaves;           // query blocks per wave
   static constexpr int kLoads = kGroupsPerBlock / kWaves;  // load instructions per wave per block
   static constexpr int kThreads = kWaves * kWave;

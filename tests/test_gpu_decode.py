@@ -152,3 +152,27 @@ def test_equal_scores_evict_newest_previous_token(kv):
         torch.cuda.synchronize()
         evicted.append(int(state.evicted_pos[0].item()))
     assert evicted == [-1, -1, -1, 2, 3, 4]
+
+
+def test_ratio_form_retention(kv):
+    """Eq. 8 as printed, k = r_d * |KV_decoding|: the caller raises the budget to ceil(r_d * tokens
+    generated so far) each step; one eviction per step keeps the decode cache at that size."""
+    shape = wl.DecodeShape("ratio", 2, 8, 2, 128, 64, 1, 0, torch.bfloat16)
+    r_d, steps = 0.4, 60
+    n_slots = int(np.ceil(r_d * steps)) + 2
+    st = wl.decode_state(shape, "cuda", n_slots=n_slots)
+    state = _make_state(kv, shape, st)
+    seqs = [OracleSeq(st, s) for s in range(2)]
+    near = []
+    for step in range(steps):
+        budget = max(1, int(np.ceil(r_d * (step + 1))))
+        state.decode_budget = budget
+        state.c_state.decode_budget = budget
+        q, kn, vn = wl.decode_inputs(shape, step, "cuda")
+        kv.decode_step(state, step, q, kn, vn)
+        torch.cuda.synchronize()
+        for s in range(2):
+            r = seqs[s].step(budget, step, q[s], kn[s], vn[s], shape.sm_scale)
+            _compare_step(state, s, r, seqs[s], near)
+            assert int((state.slot_pos[s] >= 0).sum().item()) == min(budget, step + 1)
+    assert not near, near

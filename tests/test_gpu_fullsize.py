@@ -41,7 +41,8 @@ def _properties_on_every_problem(shape, k, v, off, res):
         assert torch.equal(res.v_out[p, :, : kept[p]], v[p][:, idx])
 
 
-@pytest.mark.parametrize("name,sample", [("model32k", (0, 57, 127)), ("skew128k", (3, 31))])
+@pytest.mark.parametrize("name,sample", [("model32k", (0, 57, 127)), ("skew128k", (3, 31)),
+                                         ("sentences16k", (0, 5))])
 def test_full_workload(kv, name, sample):
     shape = wl.PREFILL_SHAPES[name]
     q, k, v, off, bud = wl.prefill_batch(shape, "cuda")
