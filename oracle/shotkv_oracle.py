@@ -224,6 +224,33 @@ def prefill_compress(q_obs, k, v, shot_offsets, budget_tokens, sm_scale, mode=SE
     return out
 
 
+def prefill_compress_per_kv_head(q_obs, k, v, shot_offsets, budget_tokens, sm_scale,
+                                 mode=SELECT_PREFIX, scores_override=None):
+    """Variant of phase 1 in which every KV head keeps its own set of shots.
+
+    Eq. 3 sums the attention weights over all H query heads, which gives one selection per layer.
+    Under grouped-query attention the KV head g is read only by the G = H / H_kv query heads
+    g*G .. g*G+G-1; restricting the head sum of Eq. 3 to that group scores each shot once per KV head,
+    and Eq. 4-6 then run independently per KV head with the same shot boundaries and the same token
+    budget.  The caches of different heads may therefore retain different shots (ragged caches).
+
+    Returns a list of H_kv results, each shaped like prefill_compress's for a single KV head
+    (k_out/v_out are [1][kept][D]).  scores_override, if given, is [H_kv][n].
+    """
+    q_obs = np.asarray(q_obs)
+    k = np.asarray(k)
+    v = np.asarray(v)
+    H = q_obs.shape[0]
+    H_kv = k.shape[0]
+    G = H // H_kv
+    results = []
+    for g in range(H_kv):
+        override = None if scores_override is None else np.asarray(scores_override)[g]
+        results.append(prefill_compress(q_obs[g * G:(g + 1) * G], k[g:g + 1], v[g:g + 1], shot_offsets,
+                                        budget_tokens, sm_scale, mode, override))
+    return results
+
+
 # --------------------------------------------------------------------------------------------------
 # Decoding phase
 # --------------------------------------------------------------------------------------------------

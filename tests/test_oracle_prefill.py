@@ -260,3 +260,54 @@ def test_workload_layouts():
             if shape.tail_tokens:
                 assert shape.n_tokens - off[-1] == shape.tail_tokens
         assert np.array_equal(wl.shot_offsets(shape, 3), wl.shot_offsets(shape, 3))
+
+
+# ---- per-KV-head variant ---------------------------------------------------------------------------
+
+def test_per_kv_head_scores_add_up_to_the_layer_score():
+    """Eq. 3 is a sum over heads, so the per-KV-head scores (each summing its own G query heads) add up
+    to the per-layer score, and each head's mass sums to G * W."""
+    rng = np.random.default_rng(11)
+    H, Hkv, D, W, N = 8, 4, 16, 4, 96
+    q, k, v = _rand_problem(rng, H, Hkv, D, W, N)
+    off = [3, 20, 41, 60, 85]
+    layer = orc.prefill_compress(q, k, v, off, 60, 0.25)
+    heads = orc.prefill_compress_per_kv_head(q, k, v, off, 60, 0.25)
+    assert len(heads) == Hkv
+    np.testing.assert_allclose(sum(h["scores"] for h in heads), layer["scores"], rtol=1e-12)
+    for h in heads:
+        assert abs(h["mass"].sum() - (H // Hkv) * W) < 1e-10
+
+
+def test_per_kv_head_selection_is_bruteforce_optimal_per_head():
+    rng = np.random.default_rng(12)
+    H, Hkv, D, W, N = 4, 2, 8, 2, 64
+    q, k, v = _rand_problem(rng, H, Hkv, D, W, N)
+    off = np.array([2, 9, 17, 22, 30, 41, 47, 56])
+    lengths = off[1:] - off[:-1]
+    n_always = 2 + (N - 56)
+    for mode in (orc.SELECT_PREFIX, orc.SELECT_FIRST_FIT):
+        heads = orc.prefill_compress_per_kv_head(q, k, v, off, n_always + 25, 0.35, mode)
+        differ = False
+        for g, h in enumerate(heads):
+            np.testing.assert_array_equal(h["selected"], orc.bruteforce_select(h["scores"], lengths, 25, mode))
+            assert h["kept_count"] <= n_always + 25
+            np.testing.assert_array_equal(h["k_out"][0], k[g][h["kept_positions"]])
+            np.testing.assert_array_equal(h["v_out"][0], v[g][h["kept_positions"]])
+            differ |= not np.array_equal(h["selected"], heads[0]["selected"])
+        assert differ or mode == orc.SELECT_FIRST_FIT   # seed chosen so the heads disagree (ragged caches)
+
+
+def test_per_kv_head_with_identical_heads_equals_the_layer_selection():
+    """Copies of one KV head (and of its query group) rank the shots identically, and the per-layer score
+    is H_kv times each head's, so both variants keep the same shots."""
+    rng = np.random.default_rng(13)
+    G, Hkv, D, W, N = 2, 3, 8, 3, 80
+    q1, k1, v1 = _rand_problem(rng, G, 1, D, W, N)
+    q, k, v = np.tile(q1, (Hkv, 1, 1)), np.tile(k1, (Hkv, 1, 1)), np.tile(v1, (Hkv, 1, 1))
+    off = [0, 11, 25, 33, 52, 70]
+    layer = orc.prefill_compress(q, k, v, off, 45, 0.3)
+    for h in orc.prefill_compress_per_kv_head(q, k, v, off, 45, 0.3):
+        np.testing.assert_array_equal(h["selected"], layer["selected"])
+        np.testing.assert_array_equal(h["kept_positions"], layer["kept_positions"])
+        np.testing.assert_allclose(h["scores"] * Hkv, layer["scores"], rtol=1e-12)
