@@ -47,6 +47,15 @@ enum { SHOTKV_BF16 = 0, SHOTKV_F32 = 1 };
  * reading, default); FIRST_FIT skips it and continues with lower-ranked shots. */
 enum { SHOTKV_SELECT_PREFIX = 0, SHOTKV_SELECT_FIRST_FIT = 1 };
 
+/* Which heads a shot's score sums over.  PER_LAYER is Eq. 3 as printed: all H query heads, one
+ * selection per (batch, layer) problem shared by its KV heads.  PER_KV_HEAD restricts the head sum to
+ * the G query heads that read a KV head, so every KV head ranks the shots, keeps its own subset under
+ * the same budget and owns its own cache ("ragged" caches); in decoding each KV head then also
+ * retains its own generated tokens by the attention of its own query group.  In this mode every
+ * per-problem output and per-sequence state array gains an H_kv dimension, as noted at each entry
+ * point; inputs are unchanged. */
+enum { SHOTKV_HEADS_PER_LAYER = 0, SHOTKV_HEADS_PER_KV_HEAD = 1 };
+
 enum {
   SHOTKV_OK = 0,
   SHOTKV_E_NULL = -1,      /* a required pointer is NULL                         */
@@ -72,6 +81,7 @@ typedef struct {
   int32_t dtype;       /* SHOTKV_BF16 or SHOTKV_F32: element type of Q, K, V      */
   float   sm_scale;    /* logits = sm_scale * <q, k>                              */
   int32_t select_mode; /* SHOTKV_SELECT_*                                          */
+  int32_t head_mode;   /* SHOTKV_HEADS_*                                           */
 } shotkv_config;
 
 SHOTKV_API const char* shotkv_strerror(int code);
@@ -117,6 +127,11 @@ SHOTKV_API size_t shotkv_prefill_workspace_bytes(const shotkv_config* cfg, int32
  *   shot_scores    [P][n_shots] float          Score(s_i)                       (may be NULL)
  *   shot_selected  [P][n_shots] uint8          1 = kept                          (may be NULL)
  *   status         [P] int32                   SHOTKV_ST_*
+ *
+ * With cfg->head_mode = SHOTKV_HEADS_PER_KV_HEAD steps (2)-(4) run once per KV head over that head's
+ * G query heads, and kept_positions is [P][H_kv][cap], kept_count [P][H_kv], shot_scores
+ * [P][H_kv][n_shots], shot_selected [P][H_kv][n_shots], status [P][H_kv]; head g of k_out/v_out holds
+ * kept_count[p][g] rows.
  */
 SHOTKV_API int shotkv_prefill_compress(const shotkv_config* cfg, int32_t P, int32_t n_tokens, int32_t n_shots,
                             const void* q_obs, const void* k, const void* v,
@@ -126,7 +141,8 @@ SHOTKV_API int shotkv_prefill_compress(const shotkv_config* cfg, int32_t P, int3
                             float* shot_scores, uint8_t* shot_selected, int32_t* status,
                             void* workspace, size_t workspace_bytes, void* stream);
 
-/* The scoring half alone (steps 1-2 above; Eq. 3): writes shot_scores [P][n_shots] and status. */
+/* The scoring half alone (steps 1-2 above; Eq. 3): writes shot_scores [P][n_shots] and status
+ * ([P][H_kv][n_shots] and [P][H_kv] in per-KV-head mode). */
 SHOTKV_API int shotkv_prefill_scores(const shotkv_config* cfg, int32_t P, int32_t n_tokens, int32_t n_shots,
                           const void* q_obs, const void* k, const int32_t* shot_offsets,
                           float* shot_scores, int32_t* status,
@@ -148,6 +164,8 @@ SHOTKV_API int shotkv_select_and_compact(const shotkv_config* cfg, int32_t P, in
  * once and remains fixed", Section 5.1).  Generated tokens live in a pool of n_slots slots per
  * sequence; slot_pos holds the generated-token index in each slot, -1 when free (initialise to -1).
  * n_slots must be >= decode_budget + 1 unless the caller guarantees fewer steps than n_slots.
+ * In per-KV-head mode prefill_count is [S][H_kv] and slot_pos [S][H_kv][n_slots]: every KV head has
+ * its own live row count and its own slot map.
  */
 typedef struct {
   const void*    k_prefill;      /* [S][H_kv][cap][D] dtype                                   */
@@ -178,6 +196,9 @@ SHOTKV_API size_t shotkv_decode_workspace_bytes(const shotkv_config* cfg, int32_
  *   token_scores [S][n_slots] float    Score(t) per slot, 0 on free slots         (may be NULL)
  *   evicted_pos  [S] int32             token index evicted this step, else -1     (may be NULL)
  *   status       [S] int32             SHOTKV_ST_*                                (required)
+ *
+ * In per-KV-head mode Eq. 7 sums over the G query heads of a KV head, Eq. 8 runs per KV head, and
+ * token_scores is [S][H_kv][n_slots], evicted_pos and status [S][H_kv].
  */
 SHOTKV_API int shotkv_decode_step(const shotkv_config* cfg, int32_t S, const shotkv_decode_state* st,
                        int32_t step_index, const void* q_new, const void* k_new, const void* v_new,

@@ -119,6 +119,7 @@ struct PrefillDims {
   int dtype;
   float sm_scale;
   int select_mode;
+  int share;  // consecutive problems that read one row of shot_offsets / budget_tokens
 };
 
 hipError_t launch_plan_chunks(const PrefillDims& d, const int32_t* shot_offsets, int32_t* status,

@@ -33,12 +33,12 @@ __device__ __forceinline__ int chunk_stride(int len, int nc) {
 }
 
 __global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
-    const int32_t* __restrict__ shot_offsets, int n_shots, int n_tokens, int chunk_keys, int max_c,
+    const int32_t* __restrict__ shot_offsets, int share, int n_shots, int n_tokens, int chunk_keys, int max_c,
     int32_t* __restrict__ status, int32_t* __restrict__ n_chunks, int32_t* __restrict__ chunk_start,
     int32_t* __restrict__ chunk_len, int32_t* __restrict__ seg_first) {
   const int p = blockIdx.x;
   const int tid = threadIdx.x;
-  const int32_t* off = shot_offsets + static_cast<size_t>(p) * (n_shots + 1);
+  const int32_t* off = shot_offsets + static_cast<size_t>(p / share) * (n_shots + 1);
   int32_t* c_start = chunk_start + static_cast<size_t>(p) * max_c;
   int32_t* c_len = chunk_len + static_cast<size_t>(p) * max_c;
   int32_t* s_first = seg_first + static_cast<size_t>(p) * (n_shots + 3);
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
 hipError_t launch_plan_chunks(const PrefillDims& d, const int32_t* shot_offsets, int32_t* status,
                               const PrefillWorkspace& w, hipStream_t s) {
   KernelTimer timer(kKernelPlan, s);
-  hipLaunchKernelGGL(plan_chunks_kernel, dim3(d.P), dim3(kPlanThreads), 0, s, shot_offsets, d.n_shots,
+  hipLaunchKernelGGL(plan_chunks_kernel, dim3(d.P), dim3(kPlanThreads), 0, s, shot_offsets, d.share, d.n_shots,
                      d.n_tokens, w.chunk_keys, w.max_c, status, w.n_chunks, w.chunk_start, w.chunk_len,
                      w.seg_first);
   return hipGetLastError();

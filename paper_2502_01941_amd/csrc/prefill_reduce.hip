@@ -78,15 +78,15 @@ __global__ __launch_bounds__(kMassThreads) void chunk_mass_kernel(const float* _
 __global__ void shot_scores_kernel(const float* __restrict__ chunk_mass,
                                    const int32_t* __restrict__ seg_first,
                                    const int32_t* __restrict__ shot_offsets,
-                                   const int32_t* __restrict__ status, int n_shots, int max_c,
-                                   float* __restrict__ shot_scores) {
+                                   const int32_t* __restrict__ status, int share, int n_shots,
+                                   int max_c, float* __restrict__ shot_scores) {
   const int p = blockIdx.y;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n_shots) return;
   float score = 0.f;
   if (status[p] == SHOTKV_ST_OK) {
     const int32_t* sf = seg_first + static_cast<size_t>(p) * (n_shots + 3);
-    const int32_t* off = shot_offsets + static_cast<size_t>(p) * (n_shots + 1);
+    const int32_t* off = shot_offsets + static_cast<size_t>(p / share) * (n_shots + 1);
     const float* mass = chunk_mass + static_cast<size_t>(p) * max_c;
     float sum = 0.f;
     for (int c = sf[i + 1]; c < sf[i + 2]; ++c) sum += mass[c];
@@ -114,7 +114,8 @@ hipError_t launch_reduce_scores(const PrefillDims& d, const int32_t* shot_offset
   if (d.n_shots > 0) {
     KernelTimer timer(kKernelShotScores, s);
     hipLaunchKernelGGL(shot_scores_kernel, dim3(ceil_div(d.n_shots, 256), d.P), dim3(256), 0, s,
-                       w.chunk_mass, w.seg_first, shot_offsets, status, d.n_shots, w.max_c, shot_scores);
+                       w.chunk_mass, w.seg_first, shot_offsets, status, d.share, d.n_shots, w.max_c,
+                       shot_scores);
   }
   return hipGetLastError();
 }

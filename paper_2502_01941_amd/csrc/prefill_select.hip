@@ -45,11 +45,11 @@ __device__ __forceinline__ bool ranks_before(float sa, int ia, float sb, int ib)
 
 __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
     const float* __restrict__ shot_scores, const int32_t* __restrict__ shot_offsets,
-    const int32_t* __restrict__ budget_tokens, int n_shots, int n_tokens, int window, int cap,
+    const int32_t* __restrict__ budget_tokens, int share, int n_shots, int n_tokens, int window, int cap,
     int select_mode, int32_t* __restrict__ kept_count, uint8_t* __restrict__ shot_selected,
     int32_t* __restrict__ status, int32_t* __restrict__ kept_positions) {
   const int p = blockIdx.x, tid = threadIdx.x;
-  const int32_t* off = shot_offsets + static_cast<size_t>(p) * (n_shots + 1);
+  const int32_t* off = shot_offsets + static_cast<size_t>(p / share) * (n_shots + 1);
   const float* scores = shot_scores + static_cast<size_t>(p) * n_shots;
   uint8_t* sel = shot_selected ? shot_selected + static_cast<size_t>(p) * n_shots : nullptr;
   int32_t* kept_pos = kept_positions + static_cast<size_t>(p) * cap;
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
   if (st == SHOTKV_ST_OK) {
     n_prefix = off[0];
     n_tail = n_tokens - off[n_shots];
-    shot_budget = min(budget_tokens[p], cap) - n_prefix - n_tail;
+    shot_budget = min(budget_tokens[p / share], cap) - n_prefix - n_tail;
     if (shot_budget < 0) st = SHOTKV_ST_BUDGET_TOO_SMALL;
   }
   if (st != SHOTKV_ST_OK) {
@@ -171,7 +171,7 @@ hipError_t launch_select_plan(const PrefillDims& d, const float* shot_scores,
                               int32_t* kept_positions, hipStream_t s) {
   KernelTimer timer(kKernelSelect, s);
   hipLaunchKernelGGL(select_plan_kernel, dim3(d.P), dim3(kSelThreads), 0, s, shot_scores, shot_offsets,
-                     budget_tokens, d.n_shots, d.n_tokens, d.W, cap, d.select_mode, kept_count,
+                     budget_tokens, d.share, d.n_shots, d.n_tokens, d.W, cap, d.select_mode, kept_count,
                      shot_selected, status, kept_positions);
   return hipGetLastError();
 }

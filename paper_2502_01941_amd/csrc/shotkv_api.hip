@@ -68,6 +68,8 @@ int check_config(const shotkv_config* cfg) {
   if (cfg->n_q_heads > 64) return SHOTKV_E_SHAPE;
   if (cfg->select_mode != SHOTKV_SELECT_PREFIX && cfg->select_mode != SHOTKV_SELECT_FIRST_FIT)
     return SHOTKV_E_SHAPE;
+  if (cfg->head_mode != SHOTKV_HEADS_PER_LAYER && cfg->head_mode != SHOTKV_HEADS_PER_KV_HEAD)
+    return SHOTKV_E_SHAPE;
   if (!(cfg->sm_scale > 0.f)) return SHOTKV_E_SHAPE;
   return SHOTKV_OK;
 }
@@ -78,12 +80,22 @@ int make_prefill_dims(const shotkv_config* cfg, int P, int n_tokens, int n_shots
   if (cfg->window < 1 || cfg->window > 64) return SHOTKV_E_SHAPE;
   const int G = cfg->n_q_heads / cfg->n_kv_heads;
   if (G * cfg->window > 256) return SHOTKV_E_SHAPE;
-  if (P < 1 || P > 32767 || n_tokens < cfg->window || n_shots < 0 || n_shots > SHOTKV_MAX_SHOTS)
-    return SHOTKV_E_SHAPE;
+  if (P < 1 || n_tokens < cfg->window || n_shots < 0 || n_shots > SHOTKV_MAX_SHOTS) return SHOTKV_E_SHAPE;
   d->P = P; d->n_tokens = n_tokens; d->n_shots = n_shots;
   d->H = cfg->n_q_heads; d->H_kv = cfg->n_kv_heads; d->G = G; d->D = cfg->head_dim;
   d->W = cfg->window; d->R = G * cfg->window; d->dtype = cfg->dtype; d->sm_scale = cfg->sm_scale;
   d->select_mode = cfg->select_mode;
+  d->share = 1;
+  if (cfg->head_mode == SHOTKV_HEADS_PER_KV_HEAD) {
+    // A KV head with its G query heads is a problem of its own: [P][H_kv][...] tensors are
+    // [P * H_kv][1][...] tensors, and only the shot boundaries and the budget are shared by the
+    // H_kv consecutive problems that came from one (batch, layer) pair.
+    d->share = d->H_kv;
+    d->P = P * d->H_kv;
+    d->H = G;
+    d->H_kv = 1;
+  }
+  if (d->P > 32767) return SHOTKV_E_SHAPE;
   return SHOTKV_OK;
 }
 
@@ -113,7 +125,7 @@ const char* shotkv_strerror(int code) {
   }
 }
 
-int32_t shotkv_abi_version(void) { return 1; }
+int32_t shotkv_abi_version(void) { return 2; }
 
 int shotkv_profile_enable(int enable) {
   std::lock_guard<std::mutex> lock(g_prof_mutex);
@@ -224,8 +236,15 @@ int shotkv_prefill_compress(const shotkv_config* cfg, int32_t P, int32_t n_token
 static int make_decode_dims(const shotkv_config* cfg, int S, int cap, int n_slots, DecodeDims* d) {
   const int rc = check_config(cfg);
   if (rc != SHOTKV_OK) return rc;
-  if (S < 1 || S > 65535 || cap < 0 || n_slots < 1) return SHOTKV_E_SHAPE;
+  if (S < 1 || cap < 0 || n_slots < 1) return SHOTKV_E_SHAPE;
   d->S = S; d->H = cfg->n_q_heads; d->H_kv = cfg->n_kv_heads; d->G = d->H / d->H_kv;
+  if (cfg->head_mode == SHOTKV_HEADS_PER_KV_HEAD) {
+    // every (sequence, KV head) pair is a sequence of its own with G query heads and one KV head
+    d->S = S * d->H_kv;
+    d->H = d->G;
+    d->H_kv = 1;
+  }
+  if (d->S > 65535) return SHOTKV_E_SHAPE;
   d->D = cfg->head_dim; d->dtype = cfg->dtype; d->cap = cap; d->n_slots = n_slots;
   d->sm_scale = cfg->sm_scale;
   const int total = cap + n_slots;

@@ -18,6 +18,7 @@ LIB_PATH = os.environ.get("SHOTKV_LIBRARY") or os.path.join(_HERE, "libshotkv.so
 
 BF16, F32 = 0, 1
 SELECT_PREFIX, SELECT_FIRST_FIT = 0, 1
+HEADS_PER_LAYER, HEADS_PER_KV_HEAD = 0, 1
 ST_OK, ST_BAD_OFFSETS, ST_BUDGET_TOO_SMALL, ST_NO_FREE_SLOT = 0, -1, -2, -3
 INT32_MAX = 2 ** 31 - 1
 
@@ -39,7 +40,8 @@ class ShotKVError(RuntimeError):
 class _Config(ctypes.Structure):
     _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("window", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("sm_scale", ctypes.c_float), ("select_mode", ctypes.c_int32)]
+                ("sm_scale", ctypes.c_float), ("select_mode", ctypes.c_int32),
+                ("head_mode", ctypes.c_int32)]
 
 
 class _DecodeState(ctypes.Structure):
@@ -120,13 +122,18 @@ def _stream():
     return torch.cuda.current_stream().cuda_stream
 
 
-def _config(H, H_kv, D, W, dtype, sm_scale, select_mode):
-    return _Config(H, H_kv, D, W, _dtype_code(dtype), float(sm_scale), int(select_mode))
+def _config(H, H_kv, D, W, dtype, sm_scale, select_mode, head_mode=HEADS_PER_LAYER):
+    return _Config(H, H_kv, D, W, _dtype_code(dtype), float(sm_scale), int(select_mode), int(head_mode))
+
+
+def _per(head_mode, H_kv):
+    """Leading shape of per-problem outputs: (P,) per layer, (P, H_kv) per KV head."""
+    return (H_kv,) if head_mode == HEADS_PER_KV_HEAD else ()
 
 
 def prefill_workspace_bytes(H, H_kv, D, W, dtype, P, n_tokens, n_shots, sm_scale=1.0,
-                            select_mode=SELECT_PREFIX) -> int:
-    cfg = _config(H, H_kv, D, W, dtype, sm_scale, select_mode)
+                            select_mode=SELECT_PREFIX, head_mode=HEADS_PER_LAYER) -> int:
+    cfg = _config(H, H_kv, D, W, dtype, sm_scale, select_mode, head_mode)
     n = load_library().shotkv_prefill_workspace_bytes(ctypes.byref(cfg), P, n_tokens, n_shots)
     if n == 0:
         raise ShotKVError("unsupported prefill shape")
@@ -137,39 +144,43 @@ def prefill_workspace_bytes(H, H_kv, D, W, dtype, P, n_tokens, n_shots, sm_scale
 class PrefillResult:
     k_out: torch.Tensor           # [P, H_kv, cap, D]
     v_out: torch.Tensor
-    kept_positions: torch.Tensor  # [P, cap] int32
-    kept_count: torch.Tensor      # [P] int32
-    shot_scores: torch.Tensor     # [P, n] float32
-    shot_selected: torch.Tensor   # [P, n] uint8
-    status: torch.Tensor          # [P] int32
+    kept_positions: torch.Tensor  # [P, cap] int32         (per-KV-head mode: [P, H_kv, cap])
+    kept_count: torch.Tensor      # [P] int32              ([P, H_kv])
+    shot_scores: torch.Tensor     # [P, n] float32         ([P, H_kv, n])
+    shot_selected: torch.Tensor   # [P, n] uint8           ([P, H_kv, n])
+    status: torch.Tensor          # [P] int32              ([P, H_kv])
 
 
-def _alloc_prefill_outputs(k, P, H_kv, cap, D, n, with_scores=True):
+def _alloc_prefill_outputs(k, P, H_kv, cap, D, n, with_scores=True, head_mode=HEADS_PER_LAYER):
     dev = k.device
+    lead = (P,) + _per(head_mode, H_kv)
     return PrefillResult(
         k_out=torch.empty((P, H_kv, cap, D), dtype=k.dtype, device=dev),
         v_out=torch.empty((P, H_kv, cap, D), dtype=k.dtype, device=dev),
-        kept_positions=torch.empty((P, cap), dtype=torch.int32, device=dev),
-        kept_count=torch.empty((P,), dtype=torch.int32, device=dev),
-        shot_scores=torch.empty((P, n), dtype=torch.float32, device=dev) if with_scores else None,
-        shot_selected=torch.empty((P, n), dtype=torch.uint8, device=dev),
-        status=torch.empty((P,), dtype=torch.int32, device=dev),
+        kept_positions=torch.empty(lead + (cap,), dtype=torch.int32, device=dev),
+        kept_count=torch.empty(lead, dtype=torch.int32, device=dev),
+        shot_scores=torch.empty(lead + (n,), dtype=torch.float32, device=dev) if with_scores else None,
+        shot_selected=torch.empty(lead + (n,), dtype=torch.uint8, device=dev),
+        status=torch.empty(lead, dtype=torch.int32, device=dev),
     )
 
 
 def prefill_compress(q_obs, k, v, shot_offsets, budget_tokens, cap, sm_scale,
-                     select_mode=SELECT_PREFIX, out: PrefillResult | None = None, workspace=None):
+                     select_mode=SELECT_PREFIX, out: PrefillResult | None = None, workspace=None,
+                     head_mode=HEADS_PER_LAYER):
     """shotkv_prefill_compress.  q_obs [P,H,W,D], k/v [P,H_kv,N,D], shot_offsets [P,n+1] int32,
     budget_tokens [P] int32 (all on the GPU).  Returns a PrefillResult; nothing is synchronised."""
     P, H, W, D = q_obs.shape
     _, H_kv, N, _ = k.shape
     n = shot_offsets.shape[1] - 1
-    cfg = _config(H, H_kv, D, W, k.dtype, sm_scale, select_mode)
+    cfg = _config(H, H_kv, D, W, k.dtype, sm_scale, select_mode, head_mode)
     lib = load_library()
+    lead = (P,) + _per(head_mode, H_kv)
     if out is None:
-        out = _alloc_prefill_outputs(k, P, H_kv, cap, D, n)
+        out = _alloc_prefill_outputs(k, P, H_kv, cap, D, n, head_mode=head_mode)
     if workspace is None:
-        workspace = torch.empty(prefill_workspace_bytes(H, H_kv, D, W, k.dtype, P, N, n, sm_scale),
+        workspace = torch.empty(prefill_workspace_bytes(H, H_kv, D, W, k.dtype, P, N, n, sm_scale,
+                                                        select_mode, head_mode),
                                 dtype=torch.uint8, device=k.device)
     rc = lib.shotkv_prefill_compress(
         ctypes.byref(cfg), P, N, n,
@@ -179,27 +190,30 @@ def prefill_compress(q_obs, k, v, shot_offsets, budget_tokens, cap, sm_scale,
         _ptr(budget_tokens, torch.int32, (P,), "budget_tokens"),
         _ptr(out.k_out, k.dtype, (P, H_kv, cap, D), "k_out"),
         _ptr(out.v_out, k.dtype, (P, H_kv, cap, D), "v_out"), cap,
-        _ptr(out.kept_positions, torch.int32, (P, cap), "kept_positions"),
-        _ptr(out.kept_count, torch.int32, (P,), "kept_count"),
-        _ptr(out.shot_scores, torch.float32, (P, n), "shot_scores"),
-        _ptr(out.shot_selected, torch.uint8, (P, n), "shot_selected"),
-        _ptr(out.status, torch.int32, (P,), "status"),
+        _ptr(out.kept_positions, torch.int32, lead + (cap,), "kept_positions"),
+        _ptr(out.kept_count, torch.int32, lead, "kept_count"),
+        _ptr(out.shot_scores, torch.float32, lead + (n,), "shot_scores"),
+        _ptr(out.shot_selected, torch.uint8, lead + (n,), "shot_selected"),
+        _ptr(out.status, torch.int32, lead, "status"),
         _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
     _check(rc, "shotkv_prefill_compress")
     return out
 
 
-def prefill_scores(q_obs, k, shot_offsets, sm_scale, workspace=None):
-    """shotkv_prefill_scores.  Returns (shot_scores [P,n] float32, status [P] int32)."""
+def prefill_scores(q_obs, k, shot_offsets, sm_scale, workspace=None, head_mode=HEADS_PER_LAYER):
+    """shotkv_prefill_scores.  Returns (shot_scores [P,n] float32, status [P] int32); both gain an H_kv
+    dimension after P in per-KV-head mode."""
     P, H, W, D = q_obs.shape
     _, H_kv, N, _ = k.shape
     n = shot_offsets.shape[1] - 1
-    cfg = _config(H, H_kv, D, W, k.dtype, sm_scale, SELECT_PREFIX)
+    cfg = _config(H, H_kv, D, W, k.dtype, sm_scale, SELECT_PREFIX, head_mode)
     lib = load_library()
-    scores = torch.empty((P, n), dtype=torch.float32, device=k.device)
-    status = torch.empty((P,), dtype=torch.int32, device=k.device)
+    lead = (P,) + _per(head_mode, H_kv)
+    scores = torch.empty(lead + (n,), dtype=torch.float32, device=k.device)
+    status = torch.empty(lead, dtype=torch.int32, device=k.device)
     if workspace is None:
-        workspace = torch.empty(prefill_workspace_bytes(H, H_kv, D, W, k.dtype, P, N, n, sm_scale),
+        workspace = torch.empty(prefill_workspace_bytes(H, H_kv, D, W, k.dtype, P, N, n, sm_scale,
+                                                        SELECT_PREFIX, head_mode),
                                 dtype=torch.uint8, device=k.device)
     rc = lib.shotkv_prefill_scores(
         ctypes.byref(cfg), P, N, n, _ptr(q_obs, k.dtype, (P, H, W, D), "q_obs"),
@@ -211,20 +225,22 @@ def prefill_scores(q_obs, k, shot_offsets, sm_scale, workspace=None):
 
 
 def select_and_compact(shot_scores, k, v, shot_offsets, budget_tokens, cap, H, W,
-                       select_mode=SELECT_PREFIX, workspace=None):
-    """shotkv_select_and_compact from caller-supplied scores [P,n] float32.  Returns a PrefillResult
-    whose shot_scores is the input tensor."""
+                       select_mode=SELECT_PREFIX, workspace=None, head_mode=HEADS_PER_LAYER):
+    """shotkv_select_and_compact from caller-supplied scores [P,n] float32 ([P,H_kv,n] in per-KV-head
+    mode).  Returns a PrefillResult whose shot_scores is the input tensor."""
     P, H_kv, N, D = k.shape
     n = shot_offsets.shape[1] - 1
-    cfg = _config(H, H_kv, D, W, k.dtype, 1.0, select_mode)
+    cfg = _config(H, H_kv, D, W, k.dtype, 1.0, select_mode, head_mode)
     lib = load_library()
-    out = _alloc_prefill_outputs(k, P, H_kv, cap, D, n, with_scores=False)
+    lead = (P,) + _per(head_mode, H_kv)
+    out = _alloc_prefill_outputs(k, P, H_kv, cap, D, n, with_scores=False, head_mode=head_mode)
     out.shot_scores = shot_scores
     if workspace is None:
-        workspace = torch.empty(prefill_workspace_bytes(H, H_kv, D, W, k.dtype, P, N, n),
+        workspace = torch.empty(prefill_workspace_bytes(H, H_kv, D, W, k.dtype, P, N, n, 1.0, select_mode,
+                                                        head_mode),
                                 dtype=torch.uint8, device=k.device)
     rc = lib.shotkv_select_and_compact(
-        ctypes.byref(cfg), P, N, n, _ptr(shot_scores, torch.float32, (P, n), "shot_scores"),
+        ctypes.byref(cfg), P, N, n, _ptr(shot_scores, torch.float32, lead + (n,), "shot_scores"),
         _ptr(k, None, (P, H_kv, N, D), "k"), _ptr(v, k.dtype, (P, H_kv, N, D), "v"),
         _ptr(shot_offsets, torch.int32, (P, n + 1), "shot_offsets"),
         _ptr(budget_tokens, torch.int32, (P,), "budget_tokens"), _ptr(out.k_out), _ptr(out.v_out), cap,
@@ -238,7 +254,7 @@ class DecodeState:
     """Caller-owned decode buffers of one layer (see shotkv_decode_state in include/shotkv.h)."""
 
     def __init__(self, k_prefill, v_prefill, prefill_count, k_dec, v_dec, slot_pos, decode_budget,
-                 n_q_heads, sm_scale):
+                 n_q_heads, sm_scale, head_mode=HEADS_PER_LAYER):
         S, H_kv, cap, D = k_prefill.shape
         n_slots = k_dec.shape[2]
         self.S, self.H_kv, self.cap, self.D, self.n_slots = S, H_kv, cap, D, n_slots
@@ -248,22 +264,23 @@ class DecodeState:
         self.decode_budget = int(decode_budget)
         self.k_prefill, self.v_prefill, self.prefill_count = k_prefill, v_prefill, prefill_count
         self.k_dec, self.v_dec, self.slot_pos = k_dec, v_dec, slot_pos
-        self.cfg = _config(self.H, H_kv, D, 1, self.dtype, sm_scale, SELECT_PREFIX)
+        self.cfg = _config(self.H, H_kv, D, 1, self.dtype, sm_scale, SELECT_PREFIX, head_mode)
+        lead = (S,) + _per(head_mode, H_kv)
         self.c_state = _DecodeState(
             _ptr(k_prefill, self.dtype, None, "k_prefill"), _ptr(v_prefill, self.dtype, (S, H_kv, cap, D), "v_prefill"),
-            _ptr(prefill_count, torch.int32, (S,), "prefill_count"),
+            _ptr(prefill_count, torch.int32, lead, "prefill_count"),
             _ptr(k_dec, self.dtype, (S, H_kv, n_slots, D), "k_dec"),
             _ptr(v_dec, self.dtype, (S, H_kv, n_slots, D), "v_dec"),
-            _ptr(slot_pos, torch.int32, (S, n_slots), "slot_pos"), cap, n_slots, self.decode_budget)
+            _ptr(slot_pos, torch.int32, lead + (n_slots,), "slot_pos"), cap, n_slots, self.decode_budget)
         nbytes = load_library().shotkv_decode_workspace_bytes(ctypes.byref(self.cfg), S, cap, n_slots)
         if nbytes == 0:
             raise ShotKVError("unsupported decode shape")
         dev = k_prefill.device
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
         self.out = torch.empty((S, self.H, D), dtype=torch.float32, device=dev)
-        self.token_scores = torch.empty((S, n_slots), dtype=torch.float32, device=dev)
-        self.evicted_pos = torch.empty((S,), dtype=torch.int32, device=dev)
-        self.status = torch.empty((S,), dtype=torch.int32, device=dev)
+        self.token_scores = torch.empty(lead + (n_slots,), dtype=torch.float32, device=dev)
+        self.evicted_pos = torch.empty(lead, dtype=torch.int32, device=dev)
+        self.status = torch.empty(lead, dtype=torch.int32, device=dev)
 
 
 def decode_step(state: DecodeState, step_index: int, q_new, k_new, v_new, want_scores=True):

@@ -49,17 +49,18 @@ def check_selection_valid(sel, kept, pos, off, n_tokens, budget):
 
 
 def check_prefill_problem(res, p, q, k, v, off, budget, cap, sm_scale, mode=orc.SELECT_PREFIX,
-                          report=None):
+                          report=None, ref=None):
     """Compare problem p of a device PrefillResult with the oracle, element by element.
 
     Scores within SCORE_RTOL.  Selection, kept positions and compacted K/V bit-exact against the oracle
     whenever the oracle's decision margin is at least MARGIN_EXACT (with exact arithmetic the result is
     unique; a closer call may legitimately flip in fp32, is then only checked for validity and is
     recorded in `report`).  The compacted rows must always be bit-exact copies of the rows named by
-    kept_positions.
+    kept_positions.  `ref` passes in an oracle result computed elsewhere for the same inputs.
     """
     budget = min(int(budget), cap)
-    ref = oracle_prefill(q, k, v, off, budget, sm_scale, mode)
+    if ref is None:
+        ref = oracle_prefill(q, k, v, off, budget, sm_scale, mode)
     status = int(res.status[p].item())
     assert status == ref["status"], (p, status, ref["status"])
     kept = int(res.kept_count[p].item())

@@ -1,0 +1,126 @@
+"""GPU parity of the per-KV-head variant: every KV head scores the shots over its own query group,
+keeps its own subset and, in decoding, retains its own generated tokens."""
+import types
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import check_prefill_problem, to_np
+from oracle import shotkv_oracle as orc
+from paper_2502_01941_amd import workloads as wl
+from test_gpu_decode import OracleSeq, _compare_step
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kv():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2502_01941_amd import shotkv
+    shotkv.load_library()
+    return shotkv
+
+
+def _flat_view(res, P, H_kv, cap, D, n):
+    """A per-KV-head PrefillResult seen as P * H_kv single-head problems."""
+    return types.SimpleNamespace(
+        status=res.status.reshape(-1), kept_count=res.kept_count.reshape(-1),
+        shot_scores=res.shot_scores.reshape(P * H_kv, n), shot_selected=res.shot_selected.reshape(P * H_kv, n),
+        kept_positions=res.kept_positions.reshape(P * H_kv, cap),
+        k_out=res.k_out.reshape(P * H_kv, 1, cap, D), v_out=res.v_out.reshape(P * H_kv, 1, cap, D))
+
+
+@pytest.mark.parametrize("shape_name,n_problems,mode", [
+    ("tiny", 1, orc.SELECT_PREFIX), ("tiny", 1, orc.SELECT_FIRST_FIT), ("layer8k", 2, orc.SELECT_PREFIX)])
+def test_prefill_per_kv_head(kv, shape_name, n_problems, mode):
+    shape = wl.PREFILL_SHAPES[shape_name]
+    q, k, v, off, bud = wl.prefill_batch(shape, "cuda", 3, n_problems=n_problems)
+    P, H, H_kv, D, n = n_problems, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.n_shots
+    G, cap = H // H_kv, shape.budget_tokens
+    res = kv.prefill_compress(q, k, v, off, bud, cap, shape.sm_scale, select_mode=mode,
+                              head_mode=kv.HEADS_PER_KV_HEAD)
+    torch.cuda.synchronize()
+    assert res.kept_count.shape == (P, H_kv) and res.kept_positions.shape == (P, H_kv, cap)
+    view = _flat_view(res, P, H_kv, cap, D, n)
+    report, selections = [], set()
+    for p in range(P):
+        refs = orc.prefill_compress_per_kv_head(to_np(q[p]), to_np(k[p]), to_np(v[p]), off[p].cpu().numpy(),
+                                                int(bud[p].item()), shape.sm_scale, mode)
+        for g in range(H_kv):
+            check_prefill_problem(view, p * H_kv + g, q[p, g * G:(g + 1) * G], k[p, g:g + 1], v[p, g:g + 1],
+                                  off[p].cpu().numpy(), int(bud[p].item()), cap, shape.sm_scale, mode,
+                                  report=report, ref=refs[g])
+            selections.add(tuple(res.shot_selected[p, g].cpu().tolist()))
+    assert len(report) <= 1, report
+    assert len(selections) > 1          # the heads do keep different shots: the caches are ragged
+
+    # the scoring half alone and the selection half alone agree with the fused call
+    scores, status = kv.prefill_scores(q, k, off, shape.sm_scale, head_mode=kv.HEADS_PER_KV_HEAD)
+    assert torch.equal(scores, res.shot_scores) and int(status.abs().sum().item()) == 0
+    res2 = kv.select_and_compact(scores, k, v, off, bud, cap, H, shape.window, select_mode=mode,
+                                 head_mode=kv.HEADS_PER_KV_HEAD)
+    torch.cuda.synchronize()
+    assert torch.equal(res2.kept_count, res.kept_count) and torch.equal(res2.shot_selected, res.shot_selected)
+    for p in range(P):
+        for g in range(H_kv):
+            c = int(res.kept_count[p, g].item())
+            assert torch.equal(res2.kept_positions[p, g, :c], res.kept_positions[p, g, :c])
+            assert torch.equal(res2.k_out[p, g, :c], res.k_out[p, g, :c])
+            assert torch.equal(res2.v_out[p, g, :c], res.v_out[p, g, :c])
+
+
+def test_prefill_per_kv_head_bad_offsets_and_budget(kv):
+    """Data-dependent errors are reported for every head of the failing problem only."""
+    shape = wl.TINY
+    q, k, v, off, bud = wl.prefill_batch(shape, "cuda", 5, n_problems=3)
+    off = off.clone(); bud = bud.clone()
+    off[1, 2] = off[1, 1]            # not strictly increasing
+    bud[2] = 3                       # smaller than the always-kept tail
+    res = kv.prefill_compress(q, k, v, off, bud, shape.budget_tokens, shape.sm_scale,
+                              head_mode=kv.HEADS_PER_KV_HEAD)
+    torch.cuda.synchronize()
+    H_kv = shape.n_kv_heads
+    assert res.status.cpu().tolist() == [[0] * H_kv, [orc.STATUS_BAD_OFFSETS] * H_kv,
+                                         [orc.STATUS_BUDGET_TOO_SMALL] * H_kv]
+    assert res.kept_count[1:].abs().sum().item() == 0 and bool((res.kept_count[0] > 0).all())
+
+
+@pytest.mark.parametrize("dtype,D,H,H_kv", [(torch.bfloat16, 128, 16, 4), (torch.float32, 64, 4, 2)])
+def test_decode_per_kv_head_lockstep(kv, dtype, D, H, H_kv):
+    """Ragged prefill caches (a different live row count per head) and per-head retention: every
+    (sequence, KV head) pair is followed by the oracle as a sequence of its own with G query heads."""
+    S, cap, budget, steps = 2, 300, 6, 20
+    G = H // H_kv
+    shape = wl.DecodeShape("per_head", S, H, H_kv, D, cap, budget, steps, dtype)
+    st = wl.decode_state(shape, "cuda", 7)
+    gen = torch.Generator().manual_seed(99)
+    pc = torch.randint(cap // 3, cap + 1, (S, H_kv), generator=gen, dtype=torch.int32).cuda()
+    n_slots = budget + 1
+    slot_pos = torch.full((S, H_kv, n_slots), -1, dtype=torch.int32, device="cuda")
+    state = kv.DecodeState(st["k_prefill"], st["v_prefill"], pc, st["k_dec"], st["v_dec"], slot_pos, budget,
+                           H, shape.sm_scale, head_mode=kv.HEADS_PER_KV_HEAD)
+    seqs = {}
+    for s in range(S):
+        for g in range(H_kv):
+            one = {"k_prefill": st["k_prefill"][:, g:g + 1], "v_prefill": st["v_prefill"][:, g:g + 1],
+                   "prefill_count": pc[:, g], "k_dec": st["k_dec"][:, g:g + 1], "v_dec": st["v_dec"][:, g:g + 1],
+                   "slot_pos": slot_pos[:, g]}
+            seqs[(s, g)] = OracleSeq(one, s)
+    view = types.SimpleNamespace(status=state.status.view(-1), out=state.out.view(S * H_kv, G, D),
+                                 token_scores=state.token_scores.view(S * H_kv, n_slots),
+                                 evicted_pos=state.evicted_pos.view(-1), slot_pos=slot_pos.view(S * H_kv, n_slots))
+    near, evicted = [], set()
+    for step in range(steps):
+        q, kn, vn = wl.decode_inputs(shape, step, "cuda", 7)
+        kv.decode_step(state, step, q, kn, vn)
+        torch.cuda.synchronize()
+        for (s, g), seq in seqs.items():
+            r = seq.step(budget, step, q[s, g * G:(g + 1) * G], kn[s, g:g + 1], vn[s, g:g + 1], shape.sm_scale)
+            _compare_step(view, s * H_kv + g, r, seq, near)
+            assert (r["evicted_pos"] >= 0) == (step >= budget)
+        if step >= budget:
+            evicted.add(tuple(state.evicted_pos.view(-1).cpu().tolist()))
+    assert len(near) == 0, near
+    assert any(len(set(e)) > 1 for e in evicted)      # heads do evict different tokens
