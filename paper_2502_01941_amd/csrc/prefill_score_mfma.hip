@@ -76,10 +76,14 @@ __device__ __forceinline__ void issue_block(const char* __restrict__ k_plane, in
 // Fold the 16 logits a lane holds for one query (key rows 8*(v/4) + 4*half + v%4 of the block) into
 // that query's running (reference, sum) in the log2 domain: sum = sum_k 2^(z_k - reference).
 //
-// EXACT: the reference is raised to the block's maximum first (the usual online softmax).  Otherwise the
-// reference found so far is kept and the exponentials are summed against it directly - any reference
-// gives the same softmax once the chunks are combined, and one that is merely an earlier maximum is
-// safe unless a later logit exceeds it by ~2^100; that case is caught on the sum and redone exactly.
+// Any reference gives the same softmax once the chunks are combined, so the reference found so far -
+// the largest logit of some earlier block, carried over from chunk to chunk - is kept and the
+// exponentials are summed against it directly.  That is safe unless a logit exceeds the reference by
+// ~2^100 (or there is no reference yet); the case is caught on the sum, wave-uniformly, and the block
+// is then redone as the usual online-softmax update, which raises the reference to the block maximum.
+// A reference far above a chunk's logits costs nothing that the result could show: it is at most the
+// row maximum, so a term that underflows against it underflows in the normalised weight as well.
+// Both lane halves of a query always hold the same reference (the maximum is taken over both).
 template <bool MASKED, bool EXACT>
 __device__ __forceinline__ void softmax_fold(floatx16 acc, float c, int half, int rem, int key0,
                                              int last_visible, float& m_run, float& l_run) {
@@ -99,7 +103,8 @@ __device__ __forceinline__ void softmax_fold(floatx16 acc, float c, int half, in
       s1 += __builtin_amdgcn_exp2f(fmaf(acc[v + 1], c, -m_run));
     }
     const float s = s0 + s1;
-    // wave-uniform decision, so the exact path below is taken by all lanes or none
+    // wave-uniform decision, so the exact path below is taken by all lanes or none (a lane without a
+    // reference yet gets inf or NaN here)
     if (__builtin_amdgcn_ballot_w64(!(s < 0x1p100f)) == 0) {
       l_run += s;
       return;
@@ -108,6 +113,7 @@ __device__ __forceinline__ void softmax_fold(floatx16 acc, float c, int half, in
   float bm = fmaxf(acc[0], acc[1]);
 #pragma unroll
   for (int v = 2; v < 16; v += 2) bm = fmaxf(fmaxf(bm, acc[v]), acc[v + 1]);
+  bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));
   const float m_new = fmaxf(m_run, bm * c);
   const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
   const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
@@ -270,7 +276,7 @@ score_partials_mfma_kernel(
     }
   }
   int cur_buf = 0;
-  bool first_of_chunk = true;
+  bool first_block = true;
 
   while (true) {
     // this wave's share of `cur` has landed once only the loads of the queued blocks are outstanding
@@ -291,34 +297,27 @@ score_partials_mfma_kernel(
       advance();
     }
     // keys past the end of the chunk and keys a window query may not see yet are masked; both only
-    // happen in a chunk's last block or in the last W keys, so the common block takes the plain path
+    // happen in a chunk's last block or in the last W keys, so the common block takes the plain path.
+    // The workgroup's first block has no reference yet and takes the exact update straight away.
     const bool masked = cur_rem < kBlockKeys || cur_key0 + kBlockKeys - 1 > causal_base;
-    // a chunk's first block (no reference yet) and masked blocks (a lane may have seen nothing but
-    // masked keys so far) take the exact online-softmax update, the rest the cheaper one
     lds_cchar* blk = lds_base + cur_buf * kBufBytes;
-    if (masked)
+    if (first_block)
       compute_block<NQW, true, true>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
-    else if (first_of_chunk)
-      compute_block<NQW, false, true>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
+    else if (masked)
+      compute_block<NQW, true, false>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
     else
       compute_block<NQW, false, false>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
-    first_of_chunk = false;
+    first_block = false;
 
-    if (cur_rem <= kBlockKeys) {  // last block of its chunk: merge the lane halves
+    if (cur_rem <= kBlockKeys) {  // last block of its chunk: add up the lane halves (same reference)
 #pragma unroll
       for (int q = 0; q < NQW; ++q) {
-        const float mo = __shfl_xor(m_run[q], 32, kWave);
-        const float lo = __shfl_xor(l_run[q], 32, kWave);
-        const float mn = fmaxf(m_run[q], mo);
-        const float ms = (mn == -INFINITY) ? 0.f : mn;
-        const float l = l_run[q] * __builtin_amdgcn_exp2f(m_run[q] - ms) + lo * __builtin_amdgcn_exp2f(mo - ms);
-        // a + b is the same in both halves, so lanes l and l+32 hold identical results; log2(0) = -inf
-        pend[q] = mn + __builtin_amdgcn_logf(l);
-        m_run[q] = -INFINITY;
-        l_run[q] = 0.f;
+        const float l = l_run[q] + __shfl_xor(l_run[q], 32, kWave);
+        // log2(0) = -inf: a query that saw none of the chunk's keys
+        pend[q] = (l > 0.f) ? m_run[q] + __builtin_amdgcn_logf(l) : -INFINITY;
+        l_run[q] = 0.f;  // the reference carries over to the next chunk
       }
       pend_c = cur_c;
-      first_of_chunk = true;
     }
     if (n_q == 0) break;
     cur_c = q_c[0]; cur_key0 = q_key0[0]; cur_rem = q_rem[0];

@@ -53,10 +53,12 @@ MODEL32K = PrefillShape("model32k", 128, 32, 8, 128, 32, 32768, 160, torch.bfloa
 SKEW128K = PrefillShape("skew128k", 32, 32, 8, 128, 32, 131072, 400, torch.bfloat16, 2048,
                         lognormal_median=300, tail_tokens=256, skew_fraction=0.10, skew_beta=3.56)
 # Sentence-sized semantic units (the document-QA setting of the paper treats each sentence as a unit):
-# hundreds of 10-40 token spans per sequence.
+# hundreds to more than a thousand 10-40 token spans per sequence.
 SENTENCES16K = PrefillShape("sentences16k", 8, 32, 8, 128, 32, 16384, 600, torch.bfloat16,
                             (16384 * 30) // 100, len_lo=10, len_hi=40)
-PREFILL_SHAPES = {s.name: s for s in (TINY, LAYER8K, MODEL32K, SKEW128K, SENTENCES16K)}
+SENTENCES32K = PrefillShape("sentences32k", 32, 32, 8, 128, 32, 32768, 1240, torch.bfloat16,
+                            (32768 * 30) // 100, len_lo=10, len_hi=40)
+PREFILL_SHAPES = {s.name: s for s in (TINY, LAYER8K, MODEL32K, SKEW128K, SENTENCES16K, SENTENCES32K)}
 
 
 @dataclasses.dataclass(frozen=True)

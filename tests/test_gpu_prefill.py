@@ -261,3 +261,31 @@ def test_logits_far_above_the_running_reference(kv):
     assert np.all(np.isfinite(got))
     np.testing.assert_allclose(got, ref["scores"], rtol=1e-3, atol=1e-30)
     assert got[2] > 1.0 and got[0] < 1e-20                                 # the mass sits in shot 2
+
+
+def test_reference_carried_across_chunks_with_opposed_rows(kv):
+    """Half of the query rows point along +u, half along -u, and consecutive short shots alternate
+    between keys along +u and -u.  For every row the softmax reference it carries from one shot to the
+    next is alternately far above the next shot's logits (their terms nearly vanish against it) and far
+    below them (the update must fall back to the exact rescale).  Short shots make every 32-key block a
+    chunk of its own."""
+    H, Hkv, D, W, N = 32, 8, 128, 32, 2048
+    g = torch.Generator(device="cuda").manual_seed(22)
+    u = torch.zeros(D, device="cuda"); u[:4] = 0.5
+    sign = torch.where(torch.arange(W, device="cuda") % 2 == 0, 1.0, -1.0)
+    q = (4.0 * sign[None, None, :, None] * u).expand(1, H, W, D).contiguous().to(torch.bfloat16)
+    bounds = list(range(0, 1921, 24))                                      # 80 shots of 24 tokens
+    off = torch.tensor([bounds], dtype=torch.int32, device="cuda")
+    k = (0.05 * torch.randn((1, Hkv, N, D), generator=g, device="cuda"))
+    for i in range(len(bounds) - 1):
+        k[:, :, bounds[i]:bounds[i + 1], :] += (20.0 if i % 2 == 0 else -20.0) * (1 + 0.01 * i) * u
+    k = k.to(torch.bfloat16)
+    v = torch.zeros_like(k)
+    scores, status = kv.prefill_scores(q, k, off, 1.0)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0]
+    ref = oracle_prefill(q[0], k[0], v[0], off[0].cpu().numpy(), N, 1.0)
+    got = scores[0].cpu().numpy()
+    assert np.all(np.isfinite(got))
+    np.testing.assert_allclose(got, ref["scores"], rtol=1e-3, atol=1e-30)
+    assert got[-1] > 1.0 and got[-2] > 1.0                                 # the last +u and -u shots dominate
