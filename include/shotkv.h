@@ -92,10 +92,10 @@ SHOTKV_API int32_t shotkv_abi_version(void);
  * enqueues is bracketed by HIP events on the caller's stream.  shotkv_profile_read waits for the
  * recorded launches, adds their durations per kernel kind into total_ms[kind] / launches[kind]
  * (host arrays of n_kinds >= SHOTKV_KERNEL_KINDS entries) and forgets them.  Kinds, in order: chunk
- * plan, score, row statistics, chunk mass, shot scores, selection, compaction, decode partial, decode
- * finish.  Process-wide; the events are the only objects the library ever creates.
+ * plan, score, row statistics, chunk mass, shot scores and selection, compaction, decode partial,
+ * decode finish.  Process-wide; the events are the only objects the library ever creates.
  */
-#define SHOTKV_KERNEL_KINDS 9
+#define SHOTKV_KERNEL_KINDS 8
 SHOTKV_API int shotkv_profile_enable(int enable);
 SHOTKV_API int shotkv_profile_read(double* total_ms, int64_t* launches, int32_t n_kinds);
 

@@ -48,8 +48,8 @@ __host__ __device__ __forceinline__ int max_chunks(int n_tokens, int n_shots, in
 // ---- optional per-kernel timing (host) -----------------------------------------------------------
 
 enum KernelKind {
-  kKernelPlan = 0, kKernelScore, kKernelRowStats, kKernelChunkMass, kKernelShotScores, kKernelSelect,
-  kKernelCompact, kKernelDecodePartial, kKernelDecodeFinish, kKernelKinds
+  kKernelPlan = 0, kKernelScore, kKernelRowStats, kKernelChunkMass, kKernelReduceSelect, kKernelCompact,
+  kKernelDecodePartial, kKernelDecodeFinish, kKernelKinds
 };
 
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled; free otherwise.
@@ -77,21 +77,30 @@ struct PrefillWorkspace {
   // softmax partial per (problem, kv head, chunk, row): log2 of the chunk's sum of exponentials
   // (-inf for a row that sees none of the chunk's keys)
   float*   partial;       // [P][H_kv][maxC][R]
+  // the same statistic over each run of group_chunks consecutive chunks, which is what the row
+  // denominators are built from; with group_chunks == 1 it is the partial array itself
+  float*   group_stat;    // [P][H_kv][n_groups][R]
   float*   row_stat;      // [P][H_kv][R]  log2 of the row's sum of exponentials over all chunks
   float*   chunk_mass;    // [P][maxC]
   float*   scores;        // [P][n_shots]
   int32_t  max_c;
   int32_t  chunk_keys;
+  int32_t  group_chunks;  // chunks per score workgroup
+  int32_t  n_groups;      // ceil(max_c / group_chunks)
   size_t   bytes;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+int score_group_chunks(int P, int H_kv, int max_c);  // chunks per workgroup of the matrix-core score kernel
+
 inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_tokens, int n_shots,
-                                      int chunk_keys) {
+                                      bool mfma_score) {
   PrefillWorkspace w{};
-  w.chunk_keys = chunk_keys;
-  w.max_c = max_chunks(n_tokens, n_shots, chunk_keys);
+  w.chunk_keys = mfma_score ? kChunkKeys : kChunkKeysGeneric;
+  w.max_c = max_chunks(n_tokens, n_shots, w.chunk_keys);
+  w.group_chunks = mfma_score ? score_group_chunks(P, H_kv, w.max_c) : 1;
+  w.n_groups = ceil_div(w.max_c, w.group_chunks);
   size_t off = 0;
   char* b = static_cast<char*>(base);
   auto take = [&](size_t bytes) {
@@ -105,6 +114,7 @@ inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_
   w.chunk_len = reinterpret_cast<int32_t*>(take(P_ * C * 4));
   w.seg_first = reinterpret_cast<int32_t*>(take(P_ * (S + 3) * 4));
   w.partial = reinterpret_cast<float*>(take(P_ * H_kv * C * R * 4));
+  w.group_stat = w.group_chunks > 1 ? reinterpret_cast<float*>(take(P_ * H_kv * w.n_groups * R * 4)) : w.partial;
   w.row_stat = reinterpret_cast<float*>(take(P_ * H_kv * R * 4));
   w.chunk_mass = reinterpret_cast<float*>(take(P_ * C * 4));
   w.scores = reinterpret_cast<float*>(take(P_ * S * 4 + 4));
@@ -126,13 +136,14 @@ hipError_t launch_plan_chunks(const PrefillDims& d, const int32_t* shot_offsets,
                               const PrefillWorkspace& w, hipStream_t s);
 hipError_t launch_score_partials(const PrefillDims& d, const void* q_obs, const void* k,
                                  const PrefillWorkspace& w, hipStream_t s);
-hipError_t launch_reduce_scores(const PrefillDims& d, const int32_t* shot_offsets,
-                                const int32_t* status, float* shot_scores, const PrefillWorkspace& w,
-                                hipStream_t s);
-hipError_t launch_select_plan(const PrefillDims& d, const float* shot_scores,
-                              const int32_t* shot_offsets, const int32_t* budget_tokens, int cap,
-                              int32_t* kept_count, uint8_t* shot_selected, int32_t* status,
-                              int32_t* kept_positions, hipStream_t s);
+hipError_t launch_row_stats(const PrefillDims& d, const PrefillWorkspace& w, hipStream_t s);
+hipError_t launch_chunk_mass(const PrefillDims& d, const PrefillWorkspace& w, hipStream_t s);
+// Shot scores from the chunk masses (with_mass), the selection and copy plan (with_select), or both in
+// one launch.  with_mass writes shot_scores; otherwise shot_scores is read.
+hipError_t launch_reduce_select(const PrefillDims& d, bool with_mass, bool with_select, float* shot_scores,
+                                const int32_t* shot_offsets, const int32_t* budget_tokens, int cap,
+                                int32_t* kept_count, uint8_t* shot_selected, int32_t* status,
+                                int32_t* kept_positions, const PrefillWorkspace& w, hipStream_t s);
 hipError_t launch_compact(const PrefillDims& d, const void* k, const void* v, void* k_out, void* v_out,
                           int cap, const int32_t* kept_positions, const int32_t* kept_count,
                           hipStream_t s);

@@ -84,9 +84,11 @@ __device__ __forceinline__ void issue_block(const char* __restrict__ k_plane, in
 // A reference far above a chunk's logits costs nothing that the result could show: it is at most the
 // row maximum, so a term that underflows against it underflows in the normalised weight as well.
 // Both lane halves of a query always hold the same reference (the maximum is taken over both).
+// l_grp is the sum over the workgroup's finished chunks against the same reference; it follows every
+// change of the reference.
 template <bool MASKED, bool EXACT>
 __device__ __forceinline__ void softmax_fold(floatx16 acc, float c, int half, int rem, int key0,
-                                             int last_visible, float& m_run, float& l_run) {
+                                             int last_visible, float& m_run, float& l_run, float& l_grp) {
   if (MASKED) {
     // row 8*(v/4) + v%4 + 4*half is masked when it is past the chunk or past the query's position:
     // one per-lane limit, compared against compile-time row constants
@@ -124,6 +126,7 @@ __device__ __forceinline__ void softmax_fold(floatx16 acc, float c, int half, in
     s1 += __builtin_amdgcn_exp2f(fmaf(acc[v + 1], c, -m_safe));
   }
   l_run = l_run * alpha + (s0 + s1);
+  l_grp *= alpha;
   m_run = m_new;
 }
 
@@ -131,7 +134,7 @@ __device__ __forceinline__ void softmax_fold(floatx16 acc, float c, int half, in
 template <int NQW, bool MASKED, bool EXACT>
 __device__ __forceinline__ void compute_block(lds_cchar* lds_buf, const bf16x8 (&bq)[NQW][8], int lane,
                                               int qb0, int key0, int rem, int causal_base, int W, float c,
-                                              float (&m_run)[NQW], float (&l_run)[NQW]) {
+                                              float (&m_run)[NQW], float (&l_run)[NQW], float (&l_grp)[NQW]) {
   const int row = lane & 31, half = lane >> 5;
   const int base_even = row * kRowBytes + (row >> 2) * 64 + ((half ^ (row & 3)) << 4);
   lds_cchar* even = lds_buf + base_even;
@@ -151,7 +154,7 @@ __device__ __forceinline__ void compute_block(lds_cchar* lds_buf, const bf16x8 (
 #pragma unroll
   for (int q = 0; q < NQW; ++q) {
     const int last_visible = causal_base + ((qb0 + q) * 32 + row) % W;
-    softmax_fold<MASKED, EXACT>(acc[q], c, half, rem, key0, last_visible, m_run[q], l_run[q]);
+    softmax_fold<MASKED, EXACT>(acc[q], c, half, rem, key0, last_visible, m_run[q], l_run[q], l_grp[q]);
   }
 }
 
@@ -173,7 +176,7 @@ score_partials_mfma_kernel(
     const bf16_t* __restrict__ q_obs, const bf16_t* __restrict__ k, int n_tokens, int H, int H_kv, int W,
     float c, const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ chunk_start,
     const int32_t* __restrict__ chunk_len, int max_c, int chunks_per_group,
-    float* __restrict__ partial) {
+    float* __restrict__ partial, float* __restrict__ group_stat) {
   typedef PairShape<NQB> S;
   constexpr int NQW = S::kNQW;
   constexpr int R = NQB * 32;
@@ -216,9 +219,9 @@ score_partials_mfma_kernel(
   const int causal_base = n_tokens - W;
   const int g0 = wave * S::kLoads;
 
-  float m_run[NQW], l_run[NQW];
+  float m_run[NQW], l_run[NQW], l_grp[NQW];
 #pragma unroll
-  for (int q = 0; q < NQW; ++q) { m_run[q] = -INFINITY; l_run[q] = 0.f; }
+  for (int q = 0; q < NQW; ++q) { m_run[q] = -INFINITY; l_run[q] = 0.f; l_grp[q] = 0.f; }
 
   // A finished chunk's statistic, log2(sum_k 2^z_k) per query, is stored one block later, ahead of that iteration's loads: the
   // wait that follows a store also covers it, so it gets a whole block of compute to complete.  Row
@@ -302,11 +305,11 @@ score_partials_mfma_kernel(
     const bool masked = cur_rem < kBlockKeys || cur_key0 + kBlockKeys - 1 > causal_base;
     lds_cchar* blk = lds_base + cur_buf * kBufBytes;
     if (first_block)
-      compute_block<NQW, true, true>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
+      compute_block<NQW, true, true>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run, l_grp);
     else if (masked)
-      compute_block<NQW, true, false>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
+      compute_block<NQW, true, false>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run, l_grp);
     else
-      compute_block<NQW, false, false>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run);
+      compute_block<NQW, false, false>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run, l_grp);
     first_block = false;
 
     if (cur_rem <= kBlockKeys) {  // last block of its chunk: add up the lane halves (same reference)
@@ -315,6 +318,7 @@ score_partials_mfma_kernel(
         const float l = l_run[q] + __shfl_xor(l_run[q], 32, kWave);
         // log2(0) = -inf: a query that saw none of the chunk's keys
         pend[q] = (l > 0.f) ? m_run[q] + __builtin_amdgcn_logf(l) : -INFINITY;
+        l_grp[q] += l;
         l_run[q] = 0.f;  // the reference carries over to the next chunk
       }
       pend_c = cur_c;
@@ -327,23 +331,30 @@ score_partials_mfma_kernel(
     cur_buf = ring_slot(cur_buf + 1);
   }
   if (pend_c >= 0) flush();
+  // the same statistic over all of the workgroup's chunks, from which the row denominators are built
+  if (lane < 32) {
+    float* dst = group_stat + ((static_cast<size_t>(p) * H_kv + g) * gridDim.x + blockIdx.x) * R +
+                 (lane & 31) * NQB + qb0;
+#pragma unroll
+    for (int q = 0; q < NQW; ++q) dst[q] = (l_grp[q] > 0.f) ? m_run[q] + __builtin_amdgcn_logf(l_grp[q]) : -INFINITY;
+  }
 }
 
-int pick_chunks_per_group(const PrefillDims& d, int max_c) {
+}  // namespace
+
+int score_group_chunks(int P, int H_kv, int max_c) {
 #ifdef SHOTKV_CHUNKS_PER_GROUP
   return SHOTKV_CHUNKS_PER_GROUP;
 #else
   // enough workgroups to keep 256 CUs x 6 resident pairs busy several times over, while a pair
   // amortises its query registers over as many chunks as that allows
-  const long total_chunks = static_cast<long>(max_c) * d.H_kv * d.P;
+  const long total_chunks = static_cast<long>(max_c) * H_kv * P;
   long cpg = total_chunks / 16384L;
-  if (cpg < 1) cpg = 1;
+  if (cpg < 2) cpg = 2;
   if (cpg > 8) cpg = 8;
   return static_cast<int>(cpg);
 #endif
 }
-
-}  // namespace
 
 bool score_uses_mfma(const PrefillDims& d) {
   return d.dtype == SHOTKV_BF16 && d.D == kD && (d.R == 32 || d.R == 64 || d.R == 128) &&
@@ -352,14 +363,15 @@ bool score_uses_mfma(const PrefillDims& d) {
 
 hipError_t launch_score_partials_mfma(const PrefillDims& d, const void* q_obs, const void* k,
                                       const PrefillWorkspace& w, hipStream_t s) {
-  const int cpg = pick_chunks_per_group(d, w.max_c);
-  const dim3 grid(ceil_div(w.max_c, cpg), d.H_kv, d.P);
+  const int cpg = w.group_chunks;
+  const dim3 grid(w.n_groups, d.H_kv, d.P);
   const float c = d.sm_scale * kLog2e;
   KernelTimer timer(kKernelScore, s);
 #define SHOTKV_LAUNCH_SCORE(NQB)                                                                      \
   hipLaunchKernelGGL(score_partials_mfma_kernel<NQB>, grid, dim3(PairShape<NQB>::kThreads), 0, s,     \
                      static_cast<const bf16_t*>(q_obs), static_cast<const bf16_t*>(k), d.n_tokens, d.H, \
-                     d.H_kv, d.W, c, w.n_chunks, w.chunk_start, w.chunk_len, w.max_c, cpg, w.partial)
+                     d.H_kv, d.W, c, w.n_chunks, w.chunk_start, w.chunk_len, w.max_c, cpg, w.partial,      \
+                     w.group_stat)
   switch (d.R / 32) {
     case 1: SHOTKV_LAUNCH_SCORE(1); break;
     case 2: SHOTKV_LAUNCH_SCORE(2); break;

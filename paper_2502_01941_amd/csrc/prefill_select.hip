@@ -1,35 +1,47 @@
-// Whole-shot selection under the token budget and the copy plan for compaction
-// (Section 5.1, Eq. 5-6; Algorithm 1 phase 1: rank by score, keep shots in descending order while the
-// budget holds).  One workgroup per problem; ranking is a bitonic sort in LDS on the key
-// (score descending, shot index ascending), the budget walk is a prefix sum of shot lengths in rank
-// order, and the copy plan - the original position of every retained row, ascending - comes from a
-// prefix sum of kept lengths in position order.
+// Per-shot scores from the chunk masses, whole-shot selection under the token budget and the copy plan
+// for compaction (Section 5.1, Eq. 3-6; Algorithm 1 phase 1: score every shot, rank by score, keep
+// shots in descending order while the budget holds).  One workgroup per problem does all of it:
+//
+//   scores    Score(s_i) = (sum of the masses of the shot's chunks) / k_i;
+//   ranking   bitonic sort in LDS on the key (score descending, shot index ascending);
+//   budget    prefix sum of shot lengths in rank order (or the sequential first-fit walk);
+//   plan      prefix sum of kept lengths in position order gives every retained row's output slot;
+//             the original position of each output row is written in ascending order.
+//
+// The two halves can also run alone: scores only, or selection from caller-supplied scores.  All sums
+// run in a fixed order (no atomics), so results are reproducible run to run.
 #include "common.hpp"
 
 namespace shotkv {
 
 namespace {
 
-constexpr int kSelThreads = 256;
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / kWave;
 
 // block-wide exclusive scan over `n` ints stored in LDS array `a` (in place), returns the total.
-// `tmp` is kSelThreads ints of LDS.
+// `tmp` is kSelWaves + 1 ints of LDS.
 __device__ int block_exclusive_scan(int* a, int n, int* tmp) {
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int per = (n + kSelThreads - 1) / kSelThreads;
   const int lo = min(tid * per, n), hi = min(lo + per, n);
   int sum = 0;
   for (int i = lo; i < hi; ++i) sum += a[i];
-  tmp[tid] = sum;
-  __syncthreads();
-  for (int o = 1; o < kSelThreads; o <<= 1) {
-    const int add = (tid >= o) ? tmp[tid - o] : 0;
-    __syncthreads();
-    tmp[tid] += add;
-    __syncthreads();
+  int incl = sum;  // inclusive scan of the per-thread sums inside the wave
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int up = __shfl_up(incl, o, kWave);
+    if (lane >= o) incl += up;
   }
-  const int total = tmp[kSelThreads - 1];
-  int run = tmp[tid] - sum;
+  if (lane == kWave - 1) tmp[wave] = incl;
+  __syncthreads();
+  int before = 0, total = 0;
+  for (int w = 0; w < kSelWaves; ++w) {
+    const int t = tmp[w];
+    if (w < wave) before += t;
+    total += t;
+  }
+  int run = before + incl - sum;
   for (int i = lo; i < hi; ++i) {
     const int v = a[i];
     a[i] = run;
@@ -43,40 +55,68 @@ __device__ __forceinline__ bool ranks_before(float sa, int ia, float sb, int ib)
   return (sa > sb) || (sa == sb && ia < ib);
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
-    const float* __restrict__ shot_scores, const int32_t* __restrict__ shot_offsets,
-    const int32_t* __restrict__ budget_tokens, int share, int n_shots, int n_tokens, int window, int cap,
-    int select_mode, int32_t* __restrict__ kept_count, uint8_t* __restrict__ shot_selected,
-    int32_t* __restrict__ status, int32_t* __restrict__ kept_positions) {
+template <bool MASS, bool SELECT>
+__global__ __launch_bounds__(kSelThreads) void reduce_select_kernel(
+    const int32_t* __restrict__ seg_first, const float* __restrict__ chunk_mass, int max_c,
+    float* __restrict__ shot_scores,
+    const int32_t* __restrict__ shot_offsets, const int32_t* __restrict__ budget_tokens, int share,
+    int n_shots, int n_tokens, int cap, int select_mode, int32_t* __restrict__ kept_count,
+    uint8_t* __restrict__ shot_selected, int32_t* __restrict__ status,
+    int32_t* __restrict__ kept_positions) {
   const int p = blockIdx.x, tid = threadIdx.x;
-  const int32_t* off = shot_offsets + static_cast<size_t>(p / share) * (n_shots + 1);
-  const float* scores = shot_scores + static_cast<size_t>(p) * n_shots;
-  uint8_t* sel = shot_selected ? shot_selected + static_cast<size_t>(p) * n_shots : nullptr;
-  int32_t* kept_pos = kept_positions + static_cast<size_t>(p) * cap;
+  const int lane = tid % kWave, wave = tid / kWave;
+  const int32_t* off_g = shot_offsets + static_cast<size_t>(p / share) * (n_shots + 1);
+  float* scores = shot_scores + static_cast<size_t>(p) * n_shots;
 
-  __shared__ float s_score[SHOTKV_MAX_SHOTS];
+  __shared__ int s_off[SHOTKV_MAX_SHOTS + 1];
+  __shared__ int s_a[SHOTKV_MAX_SHOTS + 2];   // shot scores (as float bits) while ranking, then the scan array
   __shared__ uint16_t s_idx[SHOTKV_MAX_SHOTS];
-  __shared__ int s_a[SHOTKV_MAX_SHOTS + 2];    // scan array
   __shared__ uint8_t s_keep[SHOTKV_MAX_SHOTS];
-  __shared__ int s_tmp[kSelThreads];
+  __shared__ int s_tmp[kSelWaves + 1];
   __shared__ int s_flag;
+  float* s_score = reinterpret_cast<float*>(s_a);
 
-  // ---- validation (same rules as the chunk planner, so this kernel can run on its own) ---------
+  // ---- shot boundaries into LDS, validated: 0 <= off[0], strictly increasing, off[n] <= n_tokens --
   if (tid == 0) s_flag = 0;
   __syncthreads();
   int local_bad = 0;
   for (int i = tid; i <= n_shots; i += kSelThreads) {
-    const int o = off[i];
+    const int o = off_g[i];
+    s_off[i] = o;
     if (o < 0 || o > n_tokens) local_bad = 1;
-    if (i > 0 && o <= off[i - 1]) local_bad = 1;
+    if (i > 0 && o <= off_g[i - 1]) local_bad = 1;
   }
   if (local_bad) atomicOr(&s_flag, 1);
   __syncthreads();
-  int st = s_flag ? SHOTKV_ST_BAD_OFFSETS : SHOTKV_ST_OK;
+  const bool bad = s_flag != 0;
+
+  // ---- Eq. 3: one score per shot from the masses of its chunks ----------------------------------
+  if (MASS) {
+    if (!bad) {
+      const float* mass = chunk_mass + static_cast<size_t>(p) * max_c;
+      const int32_t* sf = seg_first + static_cast<size_t>(p) * (n_shots + 3);
+      for (int i = tid; i < n_shots; i += kSelThreads) {
+        float sum = 0.f;
+        for (int c = sf[i + 1]; c < sf[i + 2]; ++c) sum += mass[c];
+        const float sc = sum / static_cast<float>(s_off[i + 1] - s_off[i]);
+        scores[i] = sc;
+        if (SELECT) s_score[i] = sc;
+      }
+    } else {
+      for (int i = tid; i < n_shots; i += kSelThreads) scores[i] = 0.f;
+    }
+  } else if (!bad) {
+    for (int i = tid; i < n_shots; i += kSelThreads) s_score[i] = scores[i];
+  }
+  if (!SELECT) return;
+
+  uint8_t* sel = shot_selected ? shot_selected + static_cast<size_t>(p) * n_shots : nullptr;
+  int32_t* kept_pos = kept_positions + static_cast<size_t>(p) * cap;
+  int st = bad ? SHOTKV_ST_BAD_OFFSETS : SHOTKV_ST_OK;
   int shot_budget = 0, n_prefix = 0, n_tail = 0;
   if (st == SHOTKV_ST_OK) {
-    n_prefix = off[0];
-    n_tail = n_tokens - off[n_shots];
+    n_prefix = s_off[0];
+    n_tail = n_tokens - s_off[n_shots];
     shot_budget = min(budget_tokens[p / share], cap) - n_prefix - n_tail;
     if (shot_budget < 0) st = SHOTKV_ST_BUDGET_TOO_SMALL;
   }
@@ -90,7 +130,7 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
   int n_pad = 1;
   while (n_pad < n_shots) n_pad <<= 1;
   for (int i = tid; i < n_pad; i += kSelThreads) {
-    s_score[i] = (i < n_shots) ? scores[i] : -INFINITY;
+    if (i >= n_shots) s_score[i] = -INFINITY;
     s_idx[i] = static_cast<uint16_t>(i);  // padding carries indices >= n_shots, so it ranks after every real -inf score
   }
   __syncthreads();
@@ -112,10 +152,10 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
     }
   }
 
-  // ---- budget walk in rank order ------------------------------------------------------------------
+  // ---- budget walk in rank order (the scores are no longer needed: s_a becomes the scan array) ----
   for (int i = tid; i < n_shots; i += kSelThreads) {
     const int shot = s_idx[i];
-    s_a[i] = off[shot + 1] - off[shot];
+    s_a[i] = s_off[shot + 1] - s_off[shot];
     s_keep[i] = 0;
   }
   __syncthreads();
@@ -125,7 +165,7 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
     // are increasing and the kept ranks are exactly those whose inclusive sum fits
     for (int r = tid; r < n_shots; r += kSelThreads) {
       const int shot = s_idx[r];
-      const int inclusive = s_a[r] + (off[shot + 1] - off[shot]);
+      const int inclusive = s_a[r] + (s_off[shot + 1] - s_off[shot]);
       if (inclusive <= shot_budget) s_keep[shot] = 1;
     }
   } else if (tid == 0) {  // first-fit: inherently sequential over the ranking
@@ -142,8 +182,8 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
   const int n_seg = n_shots + 2;
   auto segment = [&](int s, int& src, int& len) {
     if (s == 0) { src = 0; len = n_prefix; }
-    else if (s == n_seg - 1) { src = off[n_shots]; len = n_tail; }
-    else { src = off[s - 1]; len = s_keep[s - 1] ? (off[s] - off[s - 1]) : 0; }
+    else if (s == n_seg - 1) { src = s_off[n_shots]; len = n_tail; }
+    else { src = s_off[s - 1]; len = s_keep[s - 1] ? (s_off[s] - s_off[s - 1]) : 0; }
   };
   for (int s = tid; s < n_seg; s += kSelThreads) {
     int src, len;
@@ -153,11 +193,11 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
   __syncthreads();
   const int total = block_exclusive_scan(s_a, n_seg, s_tmp);  // s_a[s] = first output row of segment s
   // every retained row's original position; one wave per segment, lanes along the rows
-  for (int s = tid / kWave; s < n_seg; s += kSelThreads / kWave) {
+  for (int s = wave; s < n_seg; s += kSelWaves) {
     int src, len;
     segment(s, src, len);
     const int dst = s_a[s];
-    for (int i = tid % kWave; i < len; i += kWave) kept_pos[dst + i] = src + i;
+    for (int i = lane; i < len; i += kWave) kept_pos[dst + i] = src + i;
   }
   if (sel) for (int i = tid; i < n_shots; i += kSelThreads) sel[i] = s_keep[i];
   if (tid == 0) { status[p] = SHOTKV_ST_OK; kept_count[p] = total; }
@@ -165,14 +205,21 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(
 
 }  // namespace
 
-hipError_t launch_select_plan(const PrefillDims& d, const float* shot_scores,
-                              const int32_t* shot_offsets, const int32_t* budget_tokens, int cap,
-                              int32_t* kept_count, uint8_t* shot_selected, int32_t* status,
-                              int32_t* kept_positions, hipStream_t s) {
-  KernelTimer timer(kKernelSelect, s);
-  hipLaunchKernelGGL(select_plan_kernel, dim3(d.P), dim3(kSelThreads), 0, s, shot_scores, shot_offsets,
-                     budget_tokens, d.share, d.n_shots, d.n_tokens, d.W, cap, d.select_mode, kept_count,
-                     shot_selected, status, kept_positions);
+hipError_t launch_reduce_select(const PrefillDims& d, bool with_mass, bool with_select, float* shot_scores,
+                                const int32_t* shot_offsets, const int32_t* budget_tokens, int cap,
+                                int32_t* kept_count, uint8_t* shot_selected, int32_t* status,
+                                int32_t* kept_positions, const PrefillWorkspace& w, hipStream_t s) {
+  KernelTimer timer(kKernelReduceSelect, s);
+#define SHOTKV_LAUNCH_RS(M, S)                                                                          \
+  hipLaunchKernelGGL((reduce_select_kernel<M, S>), dim3(d.P), dim3(kSelThreads), 0, s, w.seg_first,     \
+                     w.chunk_mass, w.max_c, shot_scores,                                                \
+                     shot_offsets, budget_tokens, d.share, d.n_shots, d.n_tokens, cap, d.select_mode,   \
+                     kept_count, shot_selected, status, kept_positions)
+  if (with_mass && with_select) SHOTKV_LAUNCH_RS(true, true);
+  else if (with_mass) SHOTKV_LAUNCH_RS(true, false);
+  else if (with_select) SHOTKV_LAUNCH_RS(false, true);
+  else return hipErrorInvalidValue;
+#undef SHOTKV_LAUNCH_RS
   return hipGetLastError();
 }
 

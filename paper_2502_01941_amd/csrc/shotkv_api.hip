@@ -100,8 +100,7 @@ int make_prefill_dims(const shotkv_config* cfg, int P, int n_tokens, int n_shots
 }
 
 PrefillWorkspace carve(const PrefillDims& d, void* base) {
-  return carve_prefill(base, d.P, d.H_kv, d.R, d.n_tokens, d.n_shots,
-                       score_uses_mfma(d) ? kChunkKeys : kChunkKeysGeneric);
+  return carve_prefill(base, d.P, d.H_kv, d.R, d.n_tokens, d.n_shots, score_uses_mfma(d));
 }
 
 int from_hip(hipError_t e) { return e == hipSuccess ? SHOTKV_OK : SHOTKV_E_LAUNCH; }
@@ -175,7 +174,11 @@ int shotkv_prefill_scores(const shotkv_config* cfg, int32_t P, int32_t n_tokens,
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = launch_plan_chunks(d, shot_offsets, status, w, s);
   if (e == hipSuccess) e = launch_score_partials(d, q_obs, k, w, s);
-  if (e == hipSuccess) e = launch_reduce_scores(d, shot_offsets, status, shot_scores, w, s);
+  if (e == hipSuccess) e = launch_row_stats(d, w, s);
+  if (e == hipSuccess) e = launch_chunk_mass(d, w, s);
+  if (e == hipSuccess)
+    e = launch_reduce_select(d, true, false, shot_scores, shot_offsets, nullptr, 0, nullptr, nullptr, status,
+                             nullptr, w, s);
   return from_hip(e);
 }
 
@@ -197,8 +200,9 @@ int shotkv_select_and_compact(const shotkv_config* cfg, int32_t P, int32_t n_tok
   const PrefillWorkspace w = carve(d, workspace);
   if (workspace_bytes < w.bytes) return SHOTKV_E_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = launch_select_plan(d, shot_scores, shot_offsets, budget_tokens, cap, kept_count,
-                                    shot_selected, status, kept_positions, s);
+  hipError_t e = launch_reduce_select(d, false, true, const_cast<float*>(shot_scores), shot_offsets,
+                                      budget_tokens, cap, kept_count, shot_selected, status, kept_positions,
+                                      w, s);
   if (e == hipSuccess) e = launch_compact(d, k, v, k_out, v_out, cap, kept_positions, kept_count, s);
   return from_hip(e);
 }
@@ -225,10 +229,11 @@ int shotkv_prefill_compress(const shotkv_config* cfg, int32_t P, int32_t n_token
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = launch_plan_chunks(d, shot_offsets, status, w, s);
   if (e == hipSuccess) e = launch_score_partials(d, q_obs, k, w, s);
-  if (e == hipSuccess) e = launch_reduce_scores(d, shot_offsets, status, scores, w, s);
+  if (e == hipSuccess) e = launch_row_stats(d, w, s);
+  if (e == hipSuccess) e = launch_chunk_mass(d, w, s);
   if (e == hipSuccess)
-    e = launch_select_plan(d, scores, shot_offsets, budget_tokens, cap, kept_count, shot_selected,
-                           status, kept_positions, s);
+    e = launch_reduce_select(d, true, true, scores, shot_offsets, budget_tokens, cap, kept_count,
+                             shot_selected, status, kept_positions, w, s);
   if (e == hipSuccess) e = launch_compact(d, k, v, k_out, v_out, cap, kept_positions, kept_count, s);
   return from_hip(e);
 }

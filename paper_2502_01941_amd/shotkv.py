@@ -29,7 +29,7 @@ EXPORTS = (
     "shotkv_profile_read",
 )
 
-KERNEL_KINDS = ("plan", "score", "row_stats", "chunk_mass", "shot_scores", "select", "compact",
+KERNEL_KINDS = ("plan", "score", "row_stats", "chunk_mass", "reduce_select", "compact",
                 "decode_partial", "decode_finish")
 
 
