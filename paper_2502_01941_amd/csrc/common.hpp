@@ -159,7 +159,6 @@ struct DecodeWorkspace {
   float2* part_ml;   // [S][H][n_splits] (max in log2 domain, sum)
   float*  part_o;    // [S][H][n_splits][D]
   float*  z_dec;     // [S][H][n_slots] scaled logits (log2 domain) of decode slots, -inf when free
-  float*  score_part; // [S][H_kv][n_slots] each KV head's share of the decode-token scores
   int32_t* new_slot;  // [S] slot chosen for the new token this step, -1 if the pool is full
   size_t  bytes;
 };
@@ -178,11 +177,16 @@ inline DecodeWorkspace carve_decode(void* base, int S, int H, int H_kv, int D, i
   w.part_ml = reinterpret_cast<float2*>(take(S_ * H * n_splits * 8));
   w.part_o = reinterpret_cast<float*>(take(S_ * H * n_splits * D * 4));
   w.z_dec = reinterpret_cast<float*>(take(S_ * H * n_slots * 4));
-  w.score_part = reinterpret_cast<float*>(take(S_ * H_kv * n_slots * 4));
   w.new_slot = reinterpret_cast<int32_t*>(take(S_ * 4));
   w.bytes = off;
   return w;
 }
+
+// Tokens per workgroup the matrix-core decode kernel can hold logits for in LDS.
+#ifndef SHOTKV_DEC_MAX_RANGE
+#define SHOTKV_DEC_MAX_RANGE 1024
+#endif
+constexpr int kDecodeMaxRange = SHOTKV_DEC_MAX_RANGE;
 
 int decode_splits(int S, int H_kv, int total_tokens);
 bool decode_uses_mfma(const DecodeDims& d);

@@ -252,75 +252,32 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
   }
 }
 
-constexpr int kFinThreads = 256;
+constexpr int kFinThreads = 1024;
 constexpr int kFinWaves = kFinThreads / kWave;
+constexpr int kFinMaxHeads = 64;
 
 // lower score first, then the newer token: the order in which decode tokens are evicted
 __device__ __forceinline__ bool evict_before(float sa, int pa, float sb, int pb) {
   return sa < sb || (sa == sb && pa > pb);
 }
 
-__global__ __launch_bounds__(kFinThreads) void decode_merge_kernel(
+// Second half of a decode step, one workgroup per sequence: merges the split partials of every query
+// head into the attention output (Eq. 9), turns the decode-slot logits into Score(t) = sum over heads of
+// the attention weight (Eq. 7) and retains under the budget (Eq. 8: the new token is exempt, the
+// lowest score goes, the newest among equals).  After the per-head statistics are known, every load
+// of the merge and of the scores is independent of the others, so the kernel costs two memory
+// round trips.
+__global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
     const float2* __restrict__ part_ml, const float* __restrict__ part_o,
-    const float* __restrict__ z_dec, const int32_t* __restrict__ slot_pos,
-    const int32_t* __restrict__ new_slot_in, int n_slots, int H, int H_kv, int D, int n_splits,
-    float* __restrict__ out, float* __restrict__ score_part) {
-  const int g = blockIdx.x, s = blockIdx.y, tid = threadIdx.x;
-  const int lane = tid % kWave, wave = tid / kWave;
-  const int G = H / H_kv;
-  __shared__ float s_M[8];
-  __shared__ float s_invL[8];
-
-  const int32_t* sp = slot_pos + static_cast<size_t>(s) * n_slots;
-  const int new_slot = new_slot_in[s];
-  const size_t head0 = static_cast<size_t>(s) * H + static_cast<size_t>(g) * G;
-  if (new_slot < 0) {  // pool full: the step is void for this sequence
-    for (int i = tid; i < G * D; i += kFinThreads) out[head0 * D + i] = 0.f;
-    return;
-  }
-
-  // global softmax statistics of this group's heads: one wave per head, lanes over the splits; each
-  // split's weight 2^(m - M) is kept so that the merge below is a plain weighted sum of loads that do
-  // not depend on one another
-  __shared__ float s_w[8][kWave];
-  for (int hl = wave; hl < G; hl += kFinWaves) {
-    const float2* ml = part_ml + (head0 + hl) * n_splits;
-    float m = -INFINITY, l = 0.f;
-    if (lane < n_splits) { const float2 x = ml[lane]; m = x.x; l = x.y; }
-    const float M = wave_max(m);
-    const float wgt = l > 0.f ? __builtin_amdgcn_exp2f(m - M) : 0.f;
-    const float L = wave_sum(l * wgt);
-    s_w[hl][lane] = wgt;
-    if (lane == 0) { s_M[hl] = M; s_invL[hl] = 1.f / L; }
-  }
-  __syncthreads();
-
-  for (int idx = tid; idx < G * D; idx += kFinThreads) {
-    const int hl = idx / D, dd = idx % D;
-    const float* po = part_o + (head0 + hl) * n_splits * D + dd;
-    float acc = 0.f;
-    for (int i = 0; i < n_splits; ++i) acc = fmaf(po[static_cast<size_t>(i) * D], s_w[hl][i], acc);
-    out[(head0 + hl) * D + dd] = acc * s_invL[hl];
-  }
-
-  // this group's share of the retention scores
-  float* part = score_part + (static_cast<size_t>(s) * H_kv + g) * n_slots;
-  for (int slot = tid; slot < n_slots; slot += kFinThreads) {
-    float share = 0.f;
-    if (slot == new_slot || sp[slot] >= 0) {
-      for (int hl = 0; hl < G; ++hl)
-        share += __builtin_amdgcn_exp2f(z_dec[(head0 + hl) * n_slots + slot] - s_M[hl]) * s_invL[hl];
-    }
-    part[slot] = share;
-  }
-}
-
-__global__ __launch_bounds__(kFinThreads) void decode_retain_kernel(
-    const float* __restrict__ score_part, int32_t* __restrict__ slot_pos,
-    const int32_t* __restrict__ new_slot_in, int n_slots, int H_kv, int budget, int step_index,
-    float* __restrict__ token_scores, int32_t* __restrict__ evicted_pos, int32_t* __restrict__ status) {
+    const float* __restrict__ z_dec, int32_t* __restrict__ slot_pos,
+    const int32_t* __restrict__ new_slot_in, int n_slots, int H, int D, int n_splits, int budget,
+    int step_index, float* __restrict__ out, float* __restrict__ token_scores,
+    int32_t* __restrict__ evicted_pos, int32_t* __restrict__ status) {
   const int s = blockIdx.x, tid = threadIdx.x;
   const int lane = tid % kWave, wave = tid / kWave;
+  __shared__ float s_M[kFinMaxHeads];
+  __shared__ float s_invL[kFinMaxHeads];
+  __shared__ float s_w[kFinMaxHeads][kWave];
   __shared__ float s_best_score[kFinWaves];
   __shared__ int s_best_pos[kFinWaves];
   __shared__ int s_best_slot[kFinWaves];
@@ -328,7 +285,9 @@ __global__ __launch_bounds__(kFinThreads) void decode_retain_kernel(
 
   int32_t* sp = slot_pos + static_cast<size_t>(s) * n_slots;
   const int new_slot = new_slot_in[s];
-  if (new_slot < 0) {
+  const size_t head0 = static_cast<size_t>(s) * H;
+  if (new_slot < 0) {  // pool full: the step is void for this sequence
+    for (int i = tid; i < H * D; i += kFinThreads) out[head0 * D + i] = 0.f;
     if (token_scores)
       for (int i = tid; i < n_slots; i += kFinThreads) token_scores[static_cast<size_t>(s) * n_slots + i] = 0.f;
     if (tid == 0) {
@@ -338,15 +297,40 @@ __global__ __launch_bounds__(kFinThreads) void decode_retain_kernel(
     return;
   }
 
+  // global softmax statistics per head: one wave per head, lanes over the splits; each split's weight
+  // 2^(m - M) is kept so that the merge below is a plain weighted sum
+  for (int h = wave; h < H; h += kFinWaves) {
+    const float2* ml = part_ml + (head0 + h) * n_splits;
+    float m = -INFINITY, l = 0.f;
+    if (lane < n_splits) { const float2 x = ml[lane]; m = x.x; l = x.y; }
+    const float M = wave_max(m);
+    const float wgt = l > 0.f ? __builtin_amdgcn_exp2f(m - M) : 0.f;
+    const float L = wave_sum(l * wgt);
+    s_w[h][lane] = wgt;
+    if (lane == 0) { s_M[h] = M; s_invL[h] = 1.f / L; }
+  }
+  __syncthreads();
+
+  // attention output
+  for (int idx = tid; idx < H * D; idx += kFinThreads) {
+    const int h = idx / D, dd = idx - h * D;
+    const float* po = part_o + (head0 + h) * n_splits * D + dd;
+    float acc = 0.f;
+    for (int i = 0; i < n_splits; ++i) acc = fmaf(po[static_cast<size_t>(i) * D], s_w[h][i], acc);
+    out[(head0 + h) * D + dd] = acc * s_invL[h];
+  }
+
+  // retention scores and the eviction candidate
   float best_score = INFINITY;
   int best_pos = -1, best_slot = -1, count = 0;
-  const float* parts = score_part + static_cast<size_t>(s) * H_kv * n_slots;
   for (int slot = tid; slot < n_slots; slot += kFinThreads) {
     const int pos = (slot == new_slot) ? step_index : sp[slot];
     float score = 0.f;
     if (pos >= 0) {
       ++count;
-      for (int gg = 0; gg < H_kv; ++gg) score += parts[static_cast<size_t>(gg) * n_slots + slot];
+      const float* z = z_dec + head0 * n_slots + slot;
+      for (int h = 0; h < H; ++h)
+        score += __builtin_amdgcn_exp2f(z[static_cast<size_t>(h) * n_slots] - s_M[h]) * s_invL[h];
       if (slot != new_slot && (best_slot < 0 || evict_before(score, pos, best_score, best_pos))) {
         best_score = score; best_pos = pos; best_slot = slot;
       }
@@ -366,7 +350,7 @@ __global__ __launch_bounds__(kFinThreads) void decode_retain_kernel(
     s_best_score[wave] = best_score; s_best_pos[wave] = best_pos;
     s_best_slot[wave] = best_slot; s_count[wave] = count;
   }
-  __syncthreads();
+  __syncthreads();  // also: every thread has read its slot_pos entries before thread 0 rewrites two
   if (tid == 0) {
     int total = s_count[0];  // this thread already holds wave 0's candidate
     for (int w = 1; w < kFinWaves; ++w) {
@@ -396,7 +380,7 @@ int decode_splits(int S, int H_kv, int total_tokens) {
   int splits = ceil_div(SHOTKV_DEC_TARGET_GROUPS, pairs);
   const int max_by_tokens = total_tokens / 128 > 0 ? total_tokens / 128 : 1;
   if (splits > max_by_tokens) splits = max_by_tokens;
-  const int min_by_range = ceil_div(total_tokens, 1024);  // the matrix-core path holds <= 1024 logits
+  const int min_by_range = ceil_div(total_tokens, kDecodeMaxRange);  // what the matrix-core path can hold
   if (splits < min_by_range) splits = min_by_range;
   if (splits > kWave) splits = kWave;
   if (splits < 1) splits = 1;
@@ -445,18 +429,11 @@ hipError_t launch_decode_partial(const DecodeDims& d, const shotkv_decode_state&
 hipError_t launch_decode_finish(const DecodeDims& d, const shotkv_decode_state& st, float* out,
                                 float* token_scores, int32_t* evicted_pos, int32_t* status,
                                 const DecodeWorkspace& w, hipStream_t s) {
-  {
-    KernelTimer timer(kKernelDecodeFinish, s);
-    hipLaunchKernelGGL(decode_merge_kernel, dim3(d.H_kv, d.S), dim3(kFinThreads), 0, s, w.part_ml,
-                       w.part_o, w.z_dec, st.slot_pos, w.new_slot, d.n_slots, d.H, d.H_kv, d.D,
-                       d.n_splits, out, w.score_part);
-  }
-  {
-    KernelTimer timer(kKernelDecodeFinish, s);
-    hipLaunchKernelGGL(decode_retain_kernel, dim3(d.S), dim3(kFinThreads), 0, s, w.score_part,
-                       st.slot_pos, w.new_slot, d.n_slots, d.H_kv, d.budget, d.step, token_scores,
-                       evicted_pos, status);
-  }
+  if (d.H > kFinMaxHeads) return hipErrorInvalidValue;
+  KernelTimer timer(kKernelDecodeFinish, s);
+  hipLaunchKernelGGL(decode_finish_kernel, dim3(d.S), dim3(kFinThreads), 0, s, w.part_ml, w.part_o, w.z_dec,
+                     st.slot_pos, w.new_slot, d.n_slots, d.H, d.D, d.n_splits, d.budget, d.step, out,
+                     token_scores, evicted_pos, status);
   return hipGetLastError();
 }
 

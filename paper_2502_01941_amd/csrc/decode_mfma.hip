@@ -2,9 +2,10 @@
 // (Section 5.1, Eq. 7 and 9: attention of the current query over prefill rows and decode slots).
 //
 // A workgroup owns one token range of one (sequence, KV head) and makes two passes over it:
-//   1. K pass: S^T[32 tokens x heads] = K_blk * Q^T with v_mfma_f32_32x32x16_bf16 (the G query heads of
-//      the group sit in the first G columns, the rest are zero); each lane fetches its token row's
-//      A operands straight from global memory (8 x 16 bytes).  The scaled logits go to LDS.
+//   1. K pass: the logits of four tokens per v_mfma_f32_16x16x32_bf16, with the head dimension cut into
+//      four pieces that sit in different operand rows/columns, so that the A operands are whole
+//      256-byte K rows fetched straight from global memory with coalesced 16-byte loads (see the
+//      kernel).  The scaled logits go to LDS.
 //   between: validity mask (free slots), per-head maximum, weights 2^(z - max) and their sums, all on
 //      the logits in LDS; decode-slot logits are also written out for the retention score (Eq. 7).
 //   2. V pass: 16 lanes stream one V row each (16 bytes per lane) and accumulate weight * V with the
@@ -20,11 +21,18 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(4))) float floatx4;
+
+// value of the lane N places away inside each row of 16 lanes (rotation, so every lane gets one)
+template <int N>
+__device__ __forceinline__ float row_rotate(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x120 | N, 0xf, 0xf, false));
+}
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kD = 128;
-constexpr int kMaxRange = 1024;  // tokens per workgroup the LDS logit buffer can hold
+constexpr int kMaxRange = kDecodeMaxRange;  // tokens per workgroup the LDS logit buffer can hold
 #ifndef SHOTKV_DEC_V_UNROLL
 #define SHOTKV_DEC_V_UNROLL 2
 #endif
@@ -56,12 +64,25 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
 
   __shared__ __attribute__((aligned(16))) float zbuf[kMaxRange][G];  // logits, then weights
-  __shared__ float s_part[kWaves][G];
   __shared__ float s_M[G];
   __shared__ float s_L[G];
   __shared__ float s_o[kWaves][G][kD];
   __shared__ int s_red[kWaves];
 
+  const size_t head0 = static_cast<size_t>(s) * H + static_cast<size_t>(g) * G;
+  // Query operands first: these loads and the one of the row count below are in flight together.
+  const int i16 = lane & 15, ksl = lane >> 4;  // A row / B column, and k-slice (8 elements) of the lane
+  const int tau = i16 >> 2, piece = i16 & 3;   // as A row; as B/C column: piece i16 >> 2, head i16 & 3
+  const int elem_off = 32 * piece + 8 * ksl;
+  constexpr int kHeadSets = (G + 3) / 4;
+  bf16x8 bq[kHeadSets];
+#pragma unroll
+  for (int m = 0; m < kHeadSets; ++m) {
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    const int hq = (i16 & 3) + 4 * m;
+    if (hq < G) raw = *reinterpret_cast<const u32x4*>(q_new + (head0 + hq) * kD + 32 * (i16 >> 2) + 8 * ksl);
+    bq[m] = __builtin_bit_cast(bf16x8, raw);
+  }
   const int32_t* sp = slot_pos + static_cast<size_t>(s) * n_slots;
   const int pc = min(prefill_count[s], cap);
   const int t_begin = split * split_tokens;
@@ -74,7 +95,6 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
   const size_t plane_p = (static_cast<size_t>(s) * H_kv + g) * cap;
   const size_t plane_d = (static_cast<size_t>(s) * H_kv + g) * n_slots;
   const size_t new_off = (static_cast<size_t>(s) * H_kv + g) * kD;
-  const size_t head0 = static_cast<size_t>(s) * H + static_cast<size_t>(g) * G;
 
   // token t of the sequence: live prefill row, occupied slot, the slot taking the new token, or nothing
   auto token_valid = [&](int t) {
@@ -85,97 +105,82 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
 
   if (new_slot >= 0 && T > 0) {
     // ---- pass 1: logits ------------------------------------------------------------------------
-    const int row = lane & 31, half = lane >> 5;
-    bf16x8 bq[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      u32x4 raw = {0u, 0u, 0u, 0u};
-      if (row < G)
-        raw = *reinterpret_cast<const u32x4*>(q_new + (head0 + row) * kD + ks * 16 + half * 8);
-      bq[ks] = __builtin_bit_cast(bf16x8, raw);
-    }
+    // One v_mfma_f32_16x16x32_bf16 scores four tokens.  Row i = 4*tau + piece of its A operand holds
+    // the 32-element piece `piece` of token `tau`, column j = 4*piece + h of its B operand the same
+    // piece of query head h, so C[4*tau + piece][4*piece + h] is that piece's share of the logit and
+    // the four shares sit in lanes 4 apart.  Laid out like this the 16 lanes that hold one token
+    // read its whole 256-byte row with one 16-byte load each: every load instruction fetches four
+    // complete rows, already in operand order.
     for (int blk = wave; blk * 32 < T; blk += kWaves) {
-      const int tt = blk * 32 + row;
-      const int t = t_begin + tt;
-      // rows past the range and free slots read the new token's key instead (always valid memory);
-      // their logits are masked between the passes
-      const bf16_t* kr = k_new + new_off;
-      bool is_new = false;
-      if (tt < T) {
-        if (t < pc) {
-          kr = k_prefill + (plane_p + t) * kD;
-        } else {
-          const int slot = t - pc;
-          is_new = slot == new_slot;
-          if (!is_new && sp[slot] >= 0) kr = k_dec + (plane_d + slot) * kD;
+      u32x4 raw[8];
+      const int tt0 = blk * 32 + tau;
+      if (t_begin + blk * 32 + 31 < pc && blk * 32 + 31 < T) {  // the whole block lies in the prefill cache
+        const bf16_t* kr = k_prefill + (plane_p + t_begin + tt0) * kD + elem_off;
+#pragma unroll
+        for (int gi = 0; gi < 8; ++gi) raw[gi] = *reinterpret_cast<const u32x4*>(kr + gi * 4 * kD);
+      } else {
+#pragma unroll
+        for (int gi = 0; gi < 8; ++gi) {
+          const int tt = tt0 + 4 * gi;
+          const int t = t_begin + tt;
+          // rows past the range and free slots read the new token's key instead (always valid
+          // memory); their logits are masked between the passes
+          const bf16_t* kr = k_new + new_off;
+          bool is_new = false;
+          if (tt < T) {
+            if (t < pc) {
+              kr = k_prefill + (plane_p + t) * kD;
+            } else {
+              const int slot = t - pc;
+              is_new = slot == new_slot;
+              if (!is_new && sp[slot] >= 0) kr = k_dec + (plane_d + slot) * kD;
+            }
+          }
+          raw[gi] = *reinterpret_cast<const u32x4*>(kr + elem_off);
+          // append: only this workgroup reads the slot this step
+          if (is_new) *reinterpret_cast<u32x4*>(k_dec + (plane_d + new_slot) * kD + elem_off) = raw[gi];
         }
       }
-      u32x4 raw[8];
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) raw[ks] = *reinterpret_cast<const u32x4*>(kr + (2 * ks + half) * 8);
-      if (is_new) {  // append: only this workgroup reads the slot this step
-        bf16_t* dst = k_dec + (plane_d + new_slot) * kD;
+      for (int gi = 0; gi < 8; ++gi) {
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) *reinterpret_cast<u32x4*>(dst + (2 * ks + half) * 8) = raw[ks];
-      }
-      floatx16 acc;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw[ks]), bq[ks], acc, 0, 0, 0);
-      // accumulator v of lane (row, half): token 8*(v/4) + 4*half + v%4 of the block, head `row`
-      if (row < G) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = blk * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-          if (m < T) zbuf[m][row] = acc[v] * scale_log2e;
+        for (int m = 0; m < kHeadSets; ++m) {
+          floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, raw[gi]), bq[m], acc, 0, 0, 0);
+          // lane (column 4*piece + h, row group ksl) holds rows 4*ksl + v: token ksl of the group, piece v
+          const int pb = i16 >> 2;
+          float z = pb == 0 ? acc[0] : pb == 1 ? acc[1] : pb == 2 ? acc[2] : acc[3];
+          z += row_rotate<4>(z);
+          z += row_rotate<8>(z);  // now every lane of the column set {h, h+4, h+8, h+12} has the logit
+          const int hq = i16 + 4 * m;
+          const int ttc = blk * 32 + 4 * gi + ksl;
+          if (i16 < 4 && hq < G && ttc < T) zbuf[ttc][hq] = z * scale_log2e;
         }
       }
     }
     __syncthreads();
 
-    // ---- between the passes: mask, maximum, weights, sums (thread tid always sees head tid % G) --
-    const int h = tid % G;
-    float mx = -INFINITY;
-    for (int idx = tid; idx < T * G; idx += kThreads) {
-      const int tt = idx / G;
-      float z = zbuf[tt][h];
-      if (!token_valid(t_begin + tt)) { z = -INFINITY; zbuf[tt][h] = z; }
-      mx = fmaxf(mx, z);
-    }
-#pragma unroll
-    for (int o = G; o < kWave; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, kWave));
-    if (lane < G) s_part[wave][lane] = mx;
-    __syncthreads();
-    if (tid < G) {
-      float m = s_part[0][tid];
-#pragma unroll
-      for (int w = 1; w < kWaves; ++w) m = fmaxf(m, s_part[w][tid]);
-      s_M[tid] = m;
-    }
-    __syncthreads();
-    const float M = s_M[h];
-    float sum = 0.f;
-    for (int idx = tid; idx < T * G; idx += kThreads) {
-      const int tt = idx / G;
-      const float z = zbuf[tt][h];
-      const int t = t_begin + tt;
-      if (t >= pc && z != -INFINITY) z_dec[(head0 + h) * n_slots + (t - pc)] = z;
-      const float p = (z == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(z - M);
-      zbuf[tt][h] = p;
-      sum += p;
-    }
-#pragma unroll
-    for (int o = G; o < kWave; o <<= 1) sum += __shfl_xor(sum, o, kWave);
-    __syncthreads();  // s_part is reused
-    if (lane < G) s_part[wave][lane] = sum;
-    __syncthreads();
-    if (tid < G) {
-      float l = 0.f;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) l += s_part[w][tid];
-      s_L[tid] = l;
+    // ---- between the passes: mask, maximum, weights and their sum; one wave per query head, so
+    //      only wave-level reductions and no workgroup barrier in between ----------------------------
+    for (int h = wave; h < G; h += kWaves) {
+      float mx = -INFINITY;
+      for (int tt = lane; tt < T; tt += kWave) {
+        float z = zbuf[tt][h];
+        if (!token_valid(t_begin + tt)) { z = -INFINITY; zbuf[tt][h] = z; }
+        mx = fmaxf(mx, z);
+      }
+      mx = wave_max(mx);
+      float sum = 0.f;
+      for (int tt = lane; tt < T; tt += kWave) {  // every lane re-reads what it wrote itself
+        const float z = zbuf[tt][h];
+        const int t = t_begin + tt;
+        if (t >= pc && z != -INFINITY) z_dec[(head0 + h) * n_slots + (t - pc)] = z;
+        const float p = (z == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(z - mx);
+        zbuf[tt][h] = p;
+        sum += p;
+      }
+      sum = wave_sum(sum);
+      if (lane == 0) { s_M[h] = mx; s_L[h] = sum; }
     }
     __syncthreads();
   } else {
@@ -192,45 +197,42 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[hh][e] = 0.f;
   if (new_slot >= 0) {
-    // kVUnroll rows per lane group are requested before any of them is used
+    // kVUnroll rows per lane group are requested before any of them is used.  A token without weight
+    // (masked, or underflowed to exactly zero) reads the new token's value row instead - always valid
+    // memory - and contributes zero times that.
     for (int tt0 = grp; tt0 < T; tt0 += kGroups * kVUnroll) {
       float p[kVUnroll][G];
       u32x4 raw[kVUnroll];
-      bool use[kVUnroll];
 #pragma unroll
       for (int u = 0; u < kVUnroll; ++u) {
         const int tt = tt0 + u * kGroups;
-        use[u] = false;
-        if (tt < T) {
+        const bool inside = tt < T;
+        const int ttc = inside ? tt : 0;
+        bool any = false;
 #pragma unroll
-          for (int hh = 0; hh < G; ++hh) { p[u][hh] = zbuf[tt][hh]; use[u] = use[u] || p[u][hh] != 0.f; }
+        for (int hh = 0; hh < G; ++hh) {
+          p[u][hh] = inside ? zbuf[ttc][hh] : 0.f;
+          any = any || p[u][hh] != 0.f;
         }
-        // a masked token, or weights that underflowed to exactly zero, contribute nothing
-        if (use[u]) {
-          const int t = t_begin + tt;
-          const bf16_t* vr;
-          const bool is_new = t >= pc && (t - pc) == new_slot;
-          if (t < pc) vr = v_prefill + (plane_p + t) * kD;
-          else if (is_new) vr = v_new + new_off;
-          else vr = v_dec + (plane_d + (t - pc)) * kD;
-          raw[u] = *reinterpret_cast<const u32x4*>(vr + lir * 8);
-          if (is_new) *reinterpret_cast<u32x4*>(v_dec + (plane_d + new_slot) * kD + lir * 8) = raw[u];
-        }
+        const int t = t_begin + ttc;
+        const bool is_new = any && t >= pc && (t - pc) == new_slot;
+        const bf16_t* vr = v_new + new_off;
+        if (any && !is_new) vr = (t < pc) ? v_prefill + (plane_p + t) * kD : v_dec + (plane_d + (t - pc)) * kD;
+        raw[u] = *reinterpret_cast<const u32x4*>(vr + lir * 8);
+        if (is_new) *reinterpret_cast<u32x4*>(v_dec + (plane_d + new_slot) * kD + lir * 8) = raw[u];
       }
 #pragma unroll
       for (int u = 0; u < kVUnroll; ++u) {
-        if (use[u]) {
-          float vf[8];
+        float vf[8];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            vf[2 * i] = __uint_as_float(raw[u][i] << 16);
-            vf[2 * i + 1] = __uint_as_float(raw[u][i] & 0xffff0000u);
-          }
-#pragma unroll
-          for (int hh = 0; hh < G; ++hh)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[hh][e] = fmaf(p[u][hh], vf[e], o[hh][e]);
+        for (int i = 0; i < 4; ++i) {
+          vf[2 * i] = __uint_as_float(raw[u][i] << 16);
+          vf[2 * i + 1] = __uint_as_float(raw[u][i] & 0xffff0000u);
         }
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[hh][e] = fmaf(p[u][hh], vf[e], o[hh][e]);
       }
     }
   }
