@@ -261,19 +261,20 @@ __device__ __forceinline__ bool evict_before(float sa, int pa, float sb, int pb)
   return sa < sb || (sa == sb && pa > pb);
 }
 
-// Second half of a decode step, one workgroup per sequence: merges the split partials of every query
-// head into the attention output (Eq. 9), turns the decode-slot logits into Score(t) = sum over heads of
-// the attention weight (Eq. 7) and retains under the budget (Eq. 8: the new token is exempt, the
-// lowest score goes, the newest among equals).  After the per-head statistics are known, every load
-// of the merge and of the scores is independent of the others, so the kernel costs two memory
-// round trips.
+// Second half of a decode step.  Per sequence, workgroup 0 turns the decode-slot logits into
+// Score(t) = sum over heads of the attention weight (Eq. 7) and retains under the budget (Eq. 8: the
+// new token is exempt, the lowest score goes, the newest among equals); workgroups 1.. each merge the
+// split partials of kFinHeadsPerGroup query heads into the attention output (Eq. 9).  Every workgroup
+// first derives the softmax statistics of the heads it needs from the split partials; after that all
+// of its loads are independent of one another, so the kernel costs two memory round trips.
+constexpr int kFinHeadsPerGroup = 4;
 __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
     const float2* __restrict__ part_ml, const float* __restrict__ part_o,
     const float* __restrict__ z_dec, int32_t* __restrict__ slot_pos,
     const int32_t* __restrict__ new_slot_in, int n_slots, int H, int D, int n_splits, int budget,
     int step_index, float* __restrict__ out, float* __restrict__ token_scores,
     int32_t* __restrict__ evicted_pos, int32_t* __restrict__ status) {
-  const int s = blockIdx.x, tid = threadIdx.x;
+  const int s = blockIdx.y, tid = threadIdx.x;
   const int lane = tid % kWave, wave = tid / kWave;
   __shared__ float s_M[kFinMaxHeads];
   __shared__ float s_invL[kFinMaxHeads];
@@ -286,20 +287,27 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
   int32_t* sp = slot_pos + static_cast<size_t>(s) * n_slots;
   const int new_slot = new_slot_in[s];
   const size_t head0 = static_cast<size_t>(s) * H;
+  const bool retain = blockIdx.x == 0;
+  // heads whose statistics this workgroup needs: all of them for the scores, its own for the merge
+  const int h_lo = retain ? 0 : (static_cast<int>(blockIdx.x) - 1) * kFinHeadsPerGroup;
+  const int h_hi = retain ? H : min(h_lo + kFinHeadsPerGroup, H);
   if (new_slot < 0) {  // pool full: the step is void for this sequence
-    for (int i = tid; i < H * D; i += kFinThreads) out[head0 * D + i] = 0.f;
-    if (token_scores)
-      for (int i = tid; i < n_slots; i += kFinThreads) token_scores[static_cast<size_t>(s) * n_slots + i] = 0.f;
-    if (tid == 0) {
-      status[s] = SHOTKV_ST_NO_FREE_SLOT;
-      if (evicted_pos) evicted_pos[s] = -1;
+    if (retain) {
+      if (token_scores)
+        for (int i = tid; i < n_slots; i += kFinThreads) token_scores[static_cast<size_t>(s) * n_slots + i] = 0.f;
+      if (tid == 0) {
+        status[s] = SHOTKV_ST_NO_FREE_SLOT;
+        if (evicted_pos) evicted_pos[s] = -1;
+      }
+    } else {
+      for (int i = h_lo * D + tid; i < h_hi * D; i += kFinThreads) out[head0 * D + i] = 0.f;
     }
     return;
   }
 
   // global softmax statistics per head: one wave per head, lanes over the splits; each split's weight
   // 2^(m - M) is kept so that the merge below is a plain weighted sum
-  for (int h = wave; h < H; h += kFinWaves) {
+  for (int h = h_lo + wave; h < h_hi; h += kFinWaves) {
     const float2* ml = part_ml + (head0 + h) * n_splits;
     float m = -INFINITY, l = 0.f;
     if (lane < n_splits) { const float2 x = ml[lane]; m = x.x; l = x.y; }
@@ -311,13 +319,15 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
   }
   __syncthreads();
 
-  // attention output
-  for (int idx = tid; idx < H * D; idx += kFinThreads) {
-    const int h = idx / D, dd = idx - h * D;
-    const float* po = part_o + (head0 + h) * n_splits * D + dd;
-    float acc = 0.f;
-    for (int i = 0; i < n_splits; ++i) acc = fmaf(po[static_cast<size_t>(i) * D], s_w[h][i], acc);
-    out[(head0 + h) * D + dd] = acc * s_invL[h];
+  if (!retain) {  // attention output of this workgroup's heads
+    for (int idx = h_lo * D + tid; idx < h_hi * D; idx += kFinThreads) {
+      const int h = idx / D, dd = idx - h * D;
+      const float* po = part_o + (head0 + h) * n_splits * D + dd;
+      float acc = 0.f;
+      for (int i = 0; i < n_splits; ++i) acc = fmaf(po[static_cast<size_t>(i) * D], s_w[h][i], acc);
+      out[(head0 + h) * D + dd] = acc * s_invL[h];
+    }
+    return;
   }
 
   // retention scores and the eviction candidate
@@ -431,7 +441,7 @@ hipError_t launch_decode_finish(const DecodeDims& d, const shotkv_decode_state& 
                                 const DecodeWorkspace& w, hipStream_t s) {
   if (d.H > kFinMaxHeads) return hipErrorInvalidValue;
   KernelTimer timer(kKernelDecodeFinish, s);
-  hipLaunchKernelGGL(decode_finish_kernel, dim3(d.S), dim3(kFinThreads), 0, s, w.part_ml, w.part_o, w.z_dec,
+  hipLaunchKernelGGL(decode_finish_kernel, dim3(1 + ceil_div(d.H, kFinHeadsPerGroup), d.S), dim3(kFinThreads), 0, s, w.part_ml, w.part_o, w.z_dec,
                      st.slot_pos, w.new_slot, d.n_slots, d.H, d.D, d.n_splits, d.budget, d.step, out,
                      token_scores, evicted_pos, status);
   return hipGetLastError();
