@@ -53,3 +53,24 @@ def test_null_arguments_are_rejected_before_any_launch(lib):
     rc = lib.shotkv_decode_step(ctypes.byref(cfg), 1, None, 0, None, None, None, None, None, None, None,
                                 None, 0, None)
     assert rc == -1
+
+
+def test_missing_library_fails_loudly_and_package_never_imports_the_oracle():
+    """There is no CPU fallback: without the built library the binding raises, in a fresh interpreter; and
+    nothing in the product package refers to the oracle."""
+    import subprocess
+    import sys
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "from paper_2502_01941_amd import shotkv\n"
+            "try:\n    shotkv.load_library()\nexcept shotkv.ShotKVError as e:\n    print('RAISED', e)\n"
+            "assert 'oracle' not in sys.modules and 'oracle.shotkv_oracle' not in sys.modules\n") % ROOT
+    env = dict(os.environ, SHOTKV_LIBRARY="/nonexistent/libshotkv.so")
+    out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr
+    assert "RAISED" in out.stdout and "not found" in out.stdout
+    pkg = os.path.join(ROOT, "paper_2502_01941_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "oracle/" not in text, f
