@@ -68,6 +68,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
   __shared__ float s_L[G];
   __shared__ float s_o[kWaves][G][kD];
   __shared__ int s_red[kWaves];
+  __shared__ int s_sp[kMaxRange];  // slot map of the decode slots inside this workgroup's range
 
   const size_t head0 = static_cast<size_t>(s) * H + static_cast<size_t>(g) * G;
   // Query operands first: these loads and the one of the row count below are in flight together.
@@ -84,13 +85,22 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
     bq[m] = __builtin_bit_cast(bf16x8, raw);
   }
   const int32_t* sp = slot_pos + static_cast<size_t>(s) * n_slots;
+  // Token axis of a sequence: t < cap is row t of the prefill cache (live while t < prefill_count), t >= cap
+  // is decode slot t - cap.  Nothing about the ranges or the addresses depends on prefill_count, so the
+  // first rows are requested while that count is still on its way; it only masks.
   const int pc = min(prefill_count[s], cap);
   const int t_begin = split * split_tokens;
-  const int t_end = min(t_begin + split_tokens, pc + n_slots);
+  const int t_end = min(t_begin + split_tokens, cap + n_slots);
   const int T = max(t_end - t_begin, 0);
-  // only a range that reaches into the decode slots needs to know which slot takes the new token
-  const int new_slot = (t_end > pc) ? lowest_free_slot(sp, n_slots, s_red) : n_slots;
-  if (t_end > pc && t_end == pc + n_slots && g == 0 && tid == 0) new_slot_out[s] = new_slot;
+  // Only a range that reaches into the decode slots needs the slot map: its part of it goes to LDS
+  // (so that the row fetches below do not wait on a second, dependent load), and the slot that takes
+  // the new token is found in the same round trip.
+  const int d_lo = max(t_begin - cap, 0);  // decode slots [d_lo, d_lo + n_range_slots) lie in the range
+  const int n_range_slots = max(t_end - cap, 0) - d_lo;
+  if (t_end > cap)
+    for (int i = tid; i < n_range_slots; i += kThreads) s_sp[i] = sp[d_lo + i];
+  const int new_slot = (t_end > cap) ? lowest_free_slot(sp, n_slots, s_red) : n_slots;  // has barriers
+  if (t_end == cap + n_slots && g == 0 && tid == 0) new_slot_out[s] = new_slot;
 
   const size_t plane_p = (static_cast<size_t>(s) * H_kv + g) * cap;
   const size_t plane_d = (static_cast<size_t>(s) * H_kv + g) * n_slots;
@@ -98,9 +108,9 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
 
   // token t of the sequence: live prefill row, occupied slot, the slot taking the new token, or nothing
   auto token_valid = [&](int t) {
-    if (t < pc) return true;
-    const int slot = t - pc;
-    return slot < n_slots && (slot == new_slot || sp[slot] >= 0);
+    if (t < cap) return t < pc;
+    const int slot = t - cap;
+    return slot < n_slots && (slot == new_slot || s_sp[slot - d_lo] >= 0);
   };
 
   if (new_slot >= 0 && T > 0) {
@@ -112,9 +122,12 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
     // read its whole 256-byte row with one 16-byte load each: every load instruction fetches four
     // complete rows, already in operand order.
     for (int blk = wave; blk * 32 < T; blk += kWaves) {
+      // a block of dead prefill rows only (count below cap) is skipped: its logits are masked between the
+      // passes whatever zbuf holds.  A wave's first block is fetched regardless, before the count is known.
+      if (blk != wave && t_begin + blk * 32 >= pc && t_begin + blk * 32 + 31 < cap) continue;
       u32x4 raw[8];
       const int tt0 = blk * 32 + tau;
-      if (t_begin + blk * 32 + 31 < pc && blk * 32 + 31 < T) {  // the whole block lies in the prefill cache
+      if (t_begin + blk * 32 + 31 < cap && blk * 32 + 31 < T) {  // the whole block lies in the prefill cache
         const bf16_t* kr = k_prefill + (plane_p + t_begin + tt0) * kD + elem_off;
 #pragma unroll
         for (int gi = 0; gi < 8; ++gi) raw[gi] = *reinterpret_cast<const u32x4*>(kr + gi * 4 * kD);
@@ -128,12 +141,12 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
           const bf16_t* kr = k_new + new_off;
           bool is_new = false;
           if (tt < T) {
-            if (t < pc) {
+            if (t < cap) {
               kr = k_prefill + (plane_p + t) * kD;
             } else {
-              const int slot = t - pc;
+              const int slot = t - cap;
               is_new = slot == new_slot;
-              if (!is_new && sp[slot] >= 0) kr = k_dec + (plane_d + slot) * kD;
+              if (!is_new && s_sp[slot - d_lo] >= 0) kr = k_dec + (plane_d + slot) * kD;
             }
           }
           raw[gi] = *reinterpret_cast<const u32x4*>(kr + elem_off);
@@ -174,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
       for (int tt = lane; tt < T; tt += kWave) {  // every lane re-reads what it wrote itself
         const float z = zbuf[tt][h];
         const int t = t_begin + tt;
-        if (t >= pc && z != -INFINITY) z_dec[(head0 + h) * n_slots + (t - pc)] = z;
+        if (t >= cap && z != -INFINITY) z_dec[(head0 + h) * n_slots + (t - cap)] = z;
         const float p = (z == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(z - mx);
         zbuf[tt][h] = p;
         sum += p;
@@ -215,9 +228,9 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
           any = any || p[u][hh] != 0.f;
         }
         const int t = t_begin + ttc;
-        const bool is_new = any && t >= pc && (t - pc) == new_slot;
+        const bool is_new = any && t >= cap && (t - cap) == new_slot;
         const bf16_t* vr = v_new + new_off;
-        if (any && !is_new) vr = (t < pc) ? v_prefill + (plane_p + t) * kD : v_dec + (plane_d + (t - pc)) * kD;
+        if (any && !is_new) vr = (t < cap) ? v_prefill + (plane_p + t) * kD : v_dec + (plane_d + (t - cap)) * kD;
         raw[u] = *reinterpret_cast<const u32x4*>(vr + lir * 8);
         if (is_new) *reinterpret_cast<u32x4*>(v_dec + (plane_d + new_slot) * kD + lir * 8) = raw[u];
       }
