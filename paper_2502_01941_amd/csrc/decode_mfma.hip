@@ -34,7 +34,7 @@ constexpr int kWaves = kThreads / kWave;
 constexpr int kD = 128;
 constexpr int kMaxRange = kDecodeMaxRange;  // tokens per workgroup the LDS logit buffer can hold
 #ifndef SHOTKV_DEC_V_UNROLL
-#define SHOTKV_DEC_V_UNROLL 2
+#define SHOTKV_DEC_V_UNROLL 4
 #endif
 constexpr int kVUnroll = SHOTKV_DEC_V_UNROLL;  // V rows a lane group has in flight
 
