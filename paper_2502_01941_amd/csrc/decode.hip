@@ -291,6 +291,19 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
   // heads whose statistics this workgroup needs: all of them for the scores, its own for the merge
   const int h_lo = retain ? 0 : (static_cast<int>(blockIdx.x) - 1) * kFinHeadsPerGroup;
   const int h_hi = retain ? H : min(h_lo + kFinHeadsPerGroup, H);
+  // (requested before the slot index above is looked at, so that the two loads travel together)
+  // global softmax statistics per head: one wave per head, lanes over the splits; each split's weight
+  // 2^(m - M) is kept so that the merge below is a plain weighted sum
+  for (int h = h_lo + wave; h < h_hi; h += kFinWaves) {
+    const float2* ml = part_ml + (head0 + h) * n_splits;
+    float m = -INFINITY, l = 0.f;
+    if (lane < n_splits) { const float2 x = ml[lane]; m = x.x; l = x.y; }
+    const float M = wave_max(m);
+    const float wgt = l > 0.f ? __builtin_amdgcn_exp2f(m - M) : 0.f;
+    const float L = wave_sum(l * wgt);
+    s_w[h][lane] = wgt;
+    if (lane == 0) { s_M[h] = M; s_invL[h] = 1.f / L; }
+  }
   if (new_slot < 0) {  // pool full: the step is void for this sequence
     if (retain) {
       if (token_scores)
@@ -305,18 +318,6 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
     return;
   }
 
-  // global softmax statistics per head: one wave per head, lanes over the splits; each split's weight
-  // 2^(m - M) is kept so that the merge below is a plain weighted sum
-  for (int h = h_lo + wave; h < h_hi; h += kFinWaves) {
-    const float2* ml = part_ml + (head0 + h) * n_splits;
-    float m = -INFINITY, l = 0.f;
-    if (lane < n_splits) { const float2 x = ml[lane]; m = x.x; l = x.y; }
-    const float M = wave_max(m);
-    const float wgt = l > 0.f ? __builtin_amdgcn_exp2f(m - M) : 0.f;
-    const float L = wave_sum(l * wgt);
-    s_w[h][lane] = wgt;
-    if (lane == 0) { s_M[h] = M; s_invL[h] = 1.f / L; }
-  }
   __syncthreads();
 
   if (!retain) {  // attention output of this workgroup's heads

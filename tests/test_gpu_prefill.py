@@ -78,6 +78,10 @@ def _ragged_problem(P, H, Hkv, D, W, N, dtype, seed, n_shots, prefix, tail_min):
     (8, 4, 64, 16, 777, torch.float32, 6),        # fp32, D=64
     (4, 4, 128, 8, 300, torch.float32, 3),        # fp32, D=128
     (8, 2, 64, 24, 500, torch.bfloat16, 5),       # bf16, D=64, W not a power of two
+    (8, 4, 128, 64, 800, torch.bfloat16, 5),      # the widest window, G=2 -> 128 rows (matrix-core path)
+    (8, 2, 128, 64, 600, torch.bfloat16, 4),      # the widest window, G=4 -> 256 rows (generic path)
+    (64, 8, 128, 32, 450, torch.bfloat16, 3),     # the most query heads, G=8 -> 256 rows
+    (4, 4, 128, 1, 200, torch.bfloat16, 3),       # a single window query
 ])
 def test_ragged_shapes(kv, H, Hkv, D, W, N, dtype, n_shots):
     P = 3
@@ -210,6 +214,26 @@ def test_many_shots_selection(kv):
         np.testing.assert_array_equal(res.kept_positions[p, :kept].cpu().numpy(), pos)
         idx = torch.from_numpy(pos).long().cuda()
         np.testing.assert_array_equal(helpers.bits(res.v_out[p, :, :kept]), helpers.bits(v[p][:, idx]))
+
+
+def test_maximum_number_of_shots_end_to_end(kv):
+    """SHOTKV_MAX_SHOTS units of 5-13 tokens through the whole path: every unit is a chunk of its own."""
+    P, H, Hkv, D, W, N, n = 1, 8, 2, 128, 32, 37000, 4096
+    g = torch.Generator(device="cuda").manual_seed(77)
+    q = torch.randn((P, H, W, D), generator=g, device="cuda").to(torch.bfloat16)
+    k = torch.randn((P, Hkv, N, D), generator=g, device="cuda").to(torch.bfloat16)
+    v = torch.randn((P, Hkv, N, D), generator=g, device="cuda").to(torch.bfloat16)
+    rng = np.random.default_rng(77)
+    off = np.concatenate([[11], 11 + np.cumsum(rng.integers(5, 14, size=n))]).astype(np.int32)
+    assert off[-1] < N - W
+    offs = torch.from_numpy(off[None]).cuda()
+    budget = N // 4
+    bud = torch.tensor([budget], dtype=torch.int32, device="cuda")
+    res = kv.prefill_compress(q, k, v, offs, bud, budget, 1.0 / math.sqrt(D))
+    torch.cuda.synchronize()
+    check_prefill_problem(res, 0, q[0], k[0], v[0], off, budget, budget, 1.0 / math.sqrt(D))
+    with pytest.raises(kv.ShotKVError):          # one more shot than the library takes
+        kv.prefill_scores(q, k, torch.zeros((1, n + 2), dtype=torch.int32, device="cuda"), 0.1)
 
 
 def test_inputs_are_not_modified_and_runs_repeat_bitwise(kv):
