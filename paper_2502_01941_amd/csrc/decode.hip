@@ -1,17 +1,18 @@
 // Decode step over the compressed cache (Section 5.1, Eq. 7-9; Algorithm 1 phase 2).
 //
-// decode_partial : split-KV attention of the new query heads over [prefill rows | decode slots].
-//                  Each workgroup owns one token range of one (sequence, KV head), streams K and V
-//                  once with 16-byte lanes, and keeps an online softmax (max, sum, weighted V) per
-//                  query head of the group.  It also appends k_new/v_new to the chosen free slot and
-//                  records the scaled logits of decode tokens for the retention score.
-// decode_merge   : one workgroup per (sequence, KV head) merges the splits of its query heads, writes
-//                  their attention output and the heads' share of Score(t) = sum_h alpha_{t,h} for
-//                  the decode tokens (Eq. 7).
-// decode_retain  : one workgroup per sequence adds the shares in fixed order and evicts the
-//                  lowest-scored earlier token when the decode cache exceeds its budget (Eq. 8 in
-//                  capacity form).  (A kernel boundary is cheaper here than a device-scope fence:
-//                  the workgroups of a sequence sit on different XCDs with separate L2 caches.)
+// decode_partial : split-KV attention of the new query heads over [prefill rows | decode slots],
+//                  shape-generic version (fp32 inputs, head_dim 64; bf16 with head_dim 128 takes the
+//                  matrix-core kernel in decode_mfma.hip).  Each workgroup owns one token range of one
+//                  (sequence, KV head), streams K and V once with 16-byte lanes, and keeps an online
+//                  softmax (max, sum, weighted V) per query head of the group.  It also appends
+//                  k_new/v_new to the chosen free slot and records the scaled logits of decode tokens
+//                  for the retention score.
+// decode_finish  : per sequence, one workgroup computes Score(t) = sum_h alpha_{t,h} for the decode
+//                  tokens (Eq. 7) and evicts the lowest-scored earlier token when the decode cache
+//                  exceeds its budget (Eq. 8 in capacity form), while further workgroups merge the
+//                  splits of four query heads each into the attention output.  (A kernel boundary
+//                  after decode_partial is cheaper than a device-scope fence: the workgroups of a
+//                  sequence sit on different XCDs with separate L2 caches.)
 #include "common.hpp"
 
 namespace shotkv {
