@@ -59,3 +59,47 @@ def test_full_workload(kv, name, sample):
         scores = res.shot_scores.cpu().numpy()
         for p in sample:
             assert scores[p][sel[p] == 1].min() > 1.2 * np.median(scores[p])
+    if name == "model32k":
+        _decode_over_the_compressed_caches(kv, shape, res, sample)
+
+
+def _decode_over_the_compressed_caches(kv, shape, res, sample):
+    """The decode half of the benchmark step: one launch over all 128 compressed caches (ragged live-row
+    counts below cap, empty slot pools of budget + 1 slots), a few steps, sampled sequences followed by
+    the oracle in lock step."""
+    from test_gpu_decode import OracleSeq, _compare_step
+    P, cap, budget = shape.n_problems, shape.budget_tokens, 1024
+    n_slots = budget + 1
+    k_dec = torch.zeros((P, shape.n_kv_heads, n_slots, shape.head_dim), dtype=shape.dtype, device="cuda")
+    v_dec = torch.zeros_like(k_dec)
+    slot_pos = torch.full((P, n_slots), -1, dtype=torch.int32, device="cuda")
+    assert int(res.kept_count.min().item()) < cap            # the caches are ragged
+    # rows past the live count are whatever the allocator left: make them hostile
+    for p in sample:
+        c = int(res.kept_count[p].item())
+        res.k_out[p, :, c:] = float("nan")
+        res.v_out[p, :, c:] = float("inf")
+    state = kv.DecodeState(res.k_out, res.v_out, res.kept_count, k_dec, v_dec, slot_pos, budget,
+                           shape.n_q_heads, shape.sm_scale)
+    st = {"k_prefill": res.k_out, "v_prefill": res.v_out, "prefill_count": res.kept_count, "k_dec": k_dec,
+          "v_dec": v_dec, "slot_pos": slot_pos}
+    seqs = {}
+    for p in sample:
+        seq = OracleSeq(st, p)
+        c = seq.pc                                              # the oracle never looks past the live rows
+        seq.kp, seq.vp = seq.kp[:, :c].copy(), seq.vp[:, :c].copy()
+        seqs[p] = seq
+    dshape = wl.DecodeShape("bench", P, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, cap, budget, 0,
+                            shape.dtype)
+    near = []
+    for step in range(4):
+        qn, kn, vn = wl.decode_inputs(dshape, step, "cuda")
+        kv.decode_step(state, step, qn, kn, vn)
+        torch.cuda.synchronize()
+        assert state.status.cpu().tolist() == [0] * P
+        assert torch.isfinite(state.out).all()
+        for p, seq in seqs.items():
+            r = seq.step(budget, step, qn[p], kn[p], vn[p], shape.sm_scale)
+            _compare_step(state, p, r, seq, near)
+    assert not near
+    assert ((slot_pos >= 0).sum(dim=1) == 4).all()
