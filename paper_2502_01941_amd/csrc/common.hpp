@@ -74,9 +74,9 @@ struct PrefillWorkspace {
   int32_t* chunk_len;     // [P][maxC] keys in the chunk (<= chunk_keys)
   int32_t* seg_first;     // [P][n_shots+3] first chunk of segment s; segment 0 = prefix, 1..n = shots,
                           //                n+1 = tail, entry n+2 = n_chunks
-  // softmax partial per (problem, kv head, chunk, row): log2 of the chunk's sum of exponentials
+  // softmax partial per (problem, chunk, kv head, row): log2 of the chunk's sum of exponentials
   // (-inf for a row that sees none of the chunk's keys)
-  float*   partial;       // [P][H_kv][maxC][R]
+  float*   partial;       // [P][maxC][H_kv][R]
   // the same statistic over each run of group_chunks consecutive chunks, which is what the row
   // denominators are built from; with group_chunks == 1 it is the partial array itself
   float*   group_stat;    // [P][H_kv][n_groups][R]

@@ -14,7 +14,8 @@ constexpr int kStatThreads = 1024;
 
 __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(const float* __restrict__ group_stat,
                                                                  const int32_t* __restrict__ n_chunks,
-                                                                 int H_kv, int R, int n_groups,
+                                                                 int H_kv, int R, size_t problem_stride,
+                                                                 size_t head_stride, size_t group_stride,
                                                                  int group_chunks,
                                                                  float* __restrict__ row_stat) {
   const int g = blockIdx.x, p = blockIdx.y;
@@ -22,15 +23,15 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(const float* __
   const int tid = threadIdx.x;
   const int r = tid % R, gl = tid / R;
   const int ng = ceil_div(n_chunks[p], group_chunks);  // groups that hold chunks
-  const float* base = group_stat + (static_cast<size_t>(p) * H_kv + g) * n_groups * R;
+  const float* base = group_stat + p * problem_stride + g * head_stride;
   // two passes over the lane's share (second one out of cache): the maximum first, then the sum of
   // 2^(x - max) with independent loads
   float M = -INFINITY;
   if (gl < nl)
-    for (int c = gl; c < ng; c += nl) M = fmaxf(M, base[static_cast<size_t>(c) * R + r]);
+    for (int c = gl; c < ng; c += nl) M = fmaxf(M, base[c * group_stride + r]);
   float L = 0.f;
   if (gl < nl && M > -INFINITY)
-    for (int c = gl; c < ng; c += nl) L += exp2f(base[static_cast<size_t>(c) * R + r] - M);  // 2^-inf = 0
+    for (int c = gl; c < ng; c += nl) L += exp2f(base[c * group_stride + r] - M);  // 2^-inf = 0
   __shared__ float sM[kStatThreads];
   __shared__ float sL[kStatThreads];
   sM[tid] = M;
@@ -48,6 +49,9 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(const float* __
 }
 
 constexpr int kMassThreads = 256;
+constexpr int kMassWaves = kMassThreads / kWave;
+constexpr int kMassPerWave = 4;  // chunks a wave has in flight
+constexpr int kMassPerBlock = kMassWaves * kMassPerWave;
 
 __global__ __launch_bounds__(kMassThreads) void chunk_mass_kernel(const float* __restrict__ partial,
                                                                   const float* __restrict__ row_stat,
@@ -56,31 +60,54 @@ __global__ __launch_bounds__(kMassThreads) void chunk_mass_kernel(const float* _
                                                                   float* __restrict__ chunk_mass) {
   const int p = blockIdx.y;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  const int c = blockIdx.x * (kMassThreads / kWave) + wave;
-  if (c >= n_chunks[p]) return;
+  const int c0 = blockIdx.x * kMassPerBlock + wave;  // this wave's chunks: c0, c0 + kMassWaves, ...
+  const int nc = n_chunks[p];
+  if (blockIdx.x * kMassPerBlock >= nc) return;
+  // a chunk's statistics of all KV heads are contiguous and line up with the row denominators
   const float* stat = row_stat + static_cast<size_t>(p) * H_kv * R;
-  float acc = 0.f;
-  for (int g = 0; g < H_kv; ++g) {
-    const float* part = partial + ((static_cast<size_t>(p) * H_kv + g) * max_c + c) * R;
-    for (int r = lane; r < R; r += kWave) acc += exp2f(part[r] - stat[g * R + r]);  // 2^-inf = 0
+  const int E = H_kv * R;
+  float acc[kMassPerWave];
+#pragma unroll
+  for (int j = 0; j < kMassPerWave; ++j) acc[j] = 0.f;
+  for (int e = lane; e < E; e += kWave) {
+    const float st = stat[e];
+    float x[kMassPerWave];
+#pragma unroll
+    for (int j = 0; j < kMassPerWave; ++j) {  // independent loads first
+      const int c = min(c0 + j * kMassWaves, nc - 1);
+      x[j] = partial[(static_cast<size_t>(p) * max_c + c) * E + e];
+    }
+#pragma unroll
+    for (int j = 0; j < kMassPerWave; ++j) acc[j] += exp2f(x[j] - st);  // 2^-inf = 0
   }
-  acc = wave_sum(acc);
-  if (lane == 0) chunk_mass[static_cast<size_t>(p) * max_c + c] = acc;
+#pragma unroll
+  for (int j = 0; j < kMassPerWave; ++j) {
+    const float total = wave_sum(acc[j]);
+    const int c = c0 + j * kMassWaves;
+    if (lane == 0 && c < nc) chunk_mass[static_cast<size_t>(p) * max_c + c] = total;
+  }
 }
 
 }  // namespace
 
 hipError_t launch_chunk_mass(const PrefillDims& d, const PrefillWorkspace& w, hipStream_t s) {
   KernelTimer timer(kKernelChunkMass, s);
-  hipLaunchKernelGGL(chunk_mass_kernel, dim3(ceil_div(w.max_c, kMassThreads / kWave), d.P), dim3(kMassThreads),
-                     0, s, w.partial, w.row_stat, w.n_chunks, d.H_kv, d.R, w.max_c, w.chunk_mass);
+  hipLaunchKernelGGL(chunk_mass_kernel, dim3(ceil_div(w.max_c, kMassPerBlock), d.P), dim3(kMassThreads), 0, s,
+                     w.partial, w.row_stat, w.n_chunks, d.H_kv, d.R, w.max_c, w.chunk_mass);
   return hipGetLastError();
 }
 
 hipError_t launch_row_stats(const PrefillDims& d, const PrefillWorkspace& w, hipStream_t s) {
   KernelTimer timer(kKernelRowStats, s);
+  // per-workgroup statistics are [P][H_kv][n_groups][R]; without them (one chunk per score workgroup)
+  // the per-chunk partials [P][max_c][H_kv][R] are read in their place
+  const bool own = w.group_stat != w.partial;
+  const size_t R = d.R, heads = d.H_kv;
+  const size_t problem_stride = own ? heads * w.n_groups * R : static_cast<size_t>(w.max_c) * heads * R;
+  const size_t head_stride = own ? w.n_groups * R : R;
+  const size_t group_stride = own ? R : heads * R;
   hipLaunchKernelGGL(row_stats_kernel, dim3(d.H_kv, d.P), dim3(kStatThreads), 0, s, w.group_stat, w.n_chunks,
-                     d.H_kv, d.R, w.n_groups, w.group_chunks, w.row_stat);
+                     d.H_kv, d.R, problem_stride, head_stride, group_stride, w.group_chunks, w.row_stat);
   return hipGetLastError();
 }
 

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(kThreads) void score_partials_generic_kernel(
   __syncthreads();
 
   const T* qbase = q_obs + (static_cast<size_t>(p) * H + static_cast<size_t>(g) * G) * W * D;
-  float* out = partial + ((static_cast<size_t>(p) * H_kv + g) * max_c + c) * R;
+  float* out = partial + ((static_cast<size_t>(p) * max_c + c) * H_kv + g) * R;
   for (int r = wave; r < R; r += kThreads / kWave) {
     const int j = r % W;
     const int last_visible = n_tokens - W + j;  // the query's own position

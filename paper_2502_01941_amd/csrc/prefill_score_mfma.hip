@@ -196,7 +196,7 @@ score_partials_mfma_kernel(
       reinterpret_cast<const char*>(k) + (static_cast<size_t>(p) * H_kv + g) * n_tokens * kRowBytes;
   const int G = H / H_kv;
   const bf16_t* q_rows = q_obs + (static_cast<size_t>(p) * H + static_cast<size_t>(g) * G) * W * kD;
-  float* out = partial + (static_cast<size_t>(p) * H_kv + g) * max_c * R;
+  float* out = partial + (static_cast<size_t>(p) * max_c * H_kv + g) * R;  // chunk c of this head: + c * H_kv * R
   const int qb0 = wave * NQW;
 
   // B operands: query row (qb0+q)*32 + lane%32, head-dim slice 16*ks + 8*(lane/32) .. +8
@@ -229,7 +229,7 @@ score_partials_mfma_kernel(
   float pend[NQW];  // log2 of the chunk's sum of exponentials per query
   int pend_c = -1;
   auto flush = [&]() {
-    float* dst = out + static_cast<size_t>(pend_c) * R + (lane & 31) * NQB + qb0;
+    float* dst = out + static_cast<size_t>(pend_c) * H_kv * R + (lane & 31) * NQB + qb0;
     if (lane < 32) {
       if (NQW == 2) *reinterpret_cast<float2*>(dst) = make_float2(pend[0], pend[NQW - 1]);
       else dst[0] = pend[0];
@@ -344,7 +344,7 @@ score_partials_mfma_kernel(
 
 int score_group_chunks(int P, int H_kv, int max_c) {
 #ifdef SHOTKV_CHUNKS_PER_GROUP
-  return SHOTKV_CHUNKS_PER_GROUP;
+  return SHOTKV_CHUNKS_PER_GROUP < 2 ? 2 : SHOTKV_CHUNKS_PER_GROUP;  // at least 2: the kernel's own statistics array
 #else
   // enough workgroups to keep 256 CUs x 6 resident pairs busy several times over, while a pair
   // amortises its query registers over as many chunks as that allows
