@@ -187,6 +187,7 @@ inline DecodeWorkspace carve_decode(void* base, int S, int H, int H_kv, int D, i
 #define SHOTKV_DEC_MAX_RANGE 1024
 #endif
 constexpr int kDecodeMaxRange = SHOTKV_DEC_MAX_RANGE;
+constexpr int kDecodeMaxSplits = 1024;  // token ranges per (sequence, KV head) the finish kernel can merge
 
 int decode_splits(int S, int H_kv, int total_tokens);
 bool decode_uses_mfma(const DecodeDims& d);

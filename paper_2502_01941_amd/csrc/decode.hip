@@ -279,7 +279,7 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
   const int lane = tid % kWave, wave = tid / kWave;
   __shared__ float s_M[kFinMaxHeads];
   __shared__ float s_invL[kFinMaxHeads];
-  __shared__ float s_w[kFinMaxHeads][kWave];
+  __shared__ float s_w[kFinHeadsPerGroup][kDecodeMaxSplits];  // merge workgroups only
   __shared__ float s_best_score[kFinWaves];
   __shared__ int s_best_pos[kFinWaves];
   __shared__ int s_best_slot[kFinWaves];
@@ -297,12 +297,17 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
   // 2^(m - M) is kept so that the merge below is a plain weighted sum
   for (int h = h_lo + wave; h < h_hi; h += kFinWaves) {
     const float2* ml = part_ml + (head0 + h) * n_splits;
-    float m = -INFINITY, l = 0.f;
-    if (lane < n_splits) { const float2 x = ml[lane]; m = x.x; l = x.y; }
-    const float M = wave_max(m);
-    const float wgt = l > 0.f ? __builtin_amdgcn_exp2f(m - M) : 0.f;
-    const float L = wave_sum(l * wgt);
-    s_w[h][lane] = wgt;
+    float M = -INFINITY;
+    for (int i = lane; i < n_splits; i += kWave) M = fmaxf(M, ml[i].x);
+    M = wave_max(M);
+    float L = 0.f;
+    for (int i = lane; i < n_splits; i += kWave) {  // second look at the same few bytes: out of cache
+      const float2 x = ml[i];
+      const float wgt = x.y > 0.f ? __builtin_amdgcn_exp2f(x.x - M) : 0.f;
+      L += x.y * wgt;
+      if (!retain) s_w[h - h_lo][i] = wgt;
+    }
+    L = wave_sum(L);
     if (lane == 0) { s_M[h] = M; s_invL[h] = 1.f / L; }
   }
   if (new_slot < 0) {  // pool full: the step is void for this sequence
@@ -326,7 +331,7 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
       const int h = idx / D, dd = idx - h * D;
       const float* po = part_o + (head0 + h) * n_splits * D + dd;
       float acc = 0.f;
-      for (int i = 0; i < n_splits; ++i) acc = fmaf(po[static_cast<size_t>(i) * D], s_w[h][i], acc);
+      for (int i = 0; i < n_splits; ++i) acc = fmaf(po[static_cast<size_t>(i) * D], s_w[h - h_lo][i], acc);
       out[(head0 + h) * D + dd] = acc * s_invL[h];
     }
     return;
@@ -387,14 +392,14 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
 
 int decode_splits(int S, int H_kv, int total_tokens) {
   // enough workgroups to fill 256 CUs several times over, but no split shorter than 128 tokens and
-  // no more splits than one wave can merge
+  // no more splits than the finish kernel takes
   const int pairs = S * H_kv;
   int splits = ceil_div(SHOTKV_DEC_TARGET_GROUPS, pairs);
   const int max_by_tokens = total_tokens / 128 > 0 ? total_tokens / 128 : 1;
   if (splits > max_by_tokens) splits = max_by_tokens;
   const int min_by_range = ceil_div(total_tokens, kDecodeMaxRange);  // what the matrix-core path can hold
   if (splits < min_by_range) splits = min_by_range;
-  if (splits > kWave) splits = kWave;
+  if (splits > kDecodeMaxSplits) splits = kDecodeMaxSplits;
   if (splits < 1) splits = 1;
   return splits;
 }
@@ -441,7 +446,7 @@ hipError_t launch_decode_partial(const DecodeDims& d, const shotkv_decode_state&
 hipError_t launch_decode_finish(const DecodeDims& d, const shotkv_decode_state& st, float* out,
                                 float* token_scores, int32_t* evicted_pos, int32_t* status,
                                 const DecodeWorkspace& w, hipStream_t s) {
-  if (d.H > kFinMaxHeads) return hipErrorInvalidValue;
+  if (d.H > kFinMaxHeads || d.n_splits > kDecodeMaxSplits) return hipErrorInvalidValue;
   KernelTimer timer(kKernelDecodeFinish, s);
   hipLaunchKernelGGL(decode_finish_kernel, dim3(1 + ceil_div(d.H, kFinHeadsPerGroup), d.S), dim3(kFinThreads), 0, s, w.part_ml, w.part_o, w.z_dec,
                      st.slot_pos, w.new_slot, d.n_slots, d.H, d.D, d.n_splits, d.budget, d.step, out,

@@ -176,3 +176,20 @@ def test_ratio_form_retention(kv):
             _compare_step(state, s, r, seqs[s], near)
             assert int((state.slot_pos[s] >= 0).sum().item()) == min(budget, step + 1)
     assert not near, near
+
+
+def test_long_cache_many_splits(kv):
+    """A 70 000-row prefill cache for one sequence: more than 64 token ranges per (sequence, KV head)."""
+    shape = wl.DecodeShape("long", 1, 32, 8, 128, 70000, 16, 0, torch.bfloat16)
+    st = wl.decode_state(shape, "cuda", 3, resident=16)
+    state = _make_state(kv, shape, st)
+    seq = OracleSeq(st, 0)
+    near = []
+    for step in range(16, 19):
+        q, kn, vn = wl.decode_inputs(shape, step, "cuda", 3)
+        kv.decode_step(state, step, q, kn, vn)
+        torch.cuda.synchronize()
+        r = seq.step(shape.decode_budget, step, q[0], kn[0], vn[0], shape.sm_scale)
+        _compare_step(state, 0, r, seq, near)
+        assert r["evicted_pos"] >= 0
+    assert not near
