@@ -133,13 +133,17 @@ def main():
     shotkv.profile_enable(True)
     shotkv.profile_read()
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # per-step spread
     torch.cuda.synchronize()
     start.record()
+    marks[0].record()
     for i in range(args.steps):
         step(args.warmup + i)
+        marks[i + 1].record()
     stop.record()
     torch.cuda.synchronize()
     ms_per_step = start.elapsed_time(stop) / args.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     prof = shotkv.profile_read()
     shotkv.profile_enable(False)
     assert int(out.status.abs().sum().item()) == 0 and int(dstate.status.abs().sum().item()) == 0
@@ -162,6 +166,7 @@ def main():
         "value": P * N / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if kvb == shape.n_kv_heads * shape.head_dim * 2 else "f32",
         "data": "synthetic",
