@@ -18,7 +18,7 @@
  *     a failed problem keeps nothing (kept_count = 0).
  *   - Tensors are dense, row-major, innermost dimension head_dim; every tensor pointer must be
  *     16-byte aligned.  "dtype" below is cfg->dtype: bf16 (2 bytes) or fp32 (4 bytes).
- *   - Supported shapes: head_dim 64 or 128; n_q_heads = G * n_kv_heads with G in {1,2,4,8};
+ *   - Supported shapes: head_dim 64 or 128; n_q_heads = G * n_kv_heads with 1 <= G <= 8, n_q_heads <= 64;
  *     1 <= window <= 64 and G * window <= 256; n_shots <= SHOTKV_MAX_SHOTS.
  *   - Two calls that share a workspace or outputs must be ordered on one stream.
  */

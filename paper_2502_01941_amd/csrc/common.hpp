@@ -125,7 +125,9 @@ inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_
 // ---- launchers implemented in the kernel files --------------------------------------------------
 
 struct PrefillDims {
-  int P, n_tokens, n_shots, H, H_kv, G, D, W, R;  // R = G * W rows per KV head
+  int P, n_tokens, n_shots, H, H_kv, G, D, W;
+  int R;       // row stride of the per-row workspace arrays: G * W, padded to 32/64/128/256 on the matrix-core path
+  int R_rows;  // G * W query rows per KV head that really exist
   int dtype;
   float sm_scale;
   int select_mode;
@@ -188,6 +190,9 @@ inline DecodeWorkspace carve_decode(void* base, int S, int H, int H_kv, int D, i
 #endif
 constexpr int kDecodeMaxRange = SHOTKV_DEC_MAX_RANGE;
 constexpr int kDecodeMaxSplits = 1024;  // token ranges per (sequence, KV head) the finish kernel can merge
+
+// query heads per KV head rounded up to 1, 2, 4 or 8: what the decode kernels are instantiated for
+inline int padded_group(int G) { return G <= 1 ? 1 : G <= 2 ? 2 : G <= 4 ? 4 : G <= 8 ? 8 : 0; }
 
 int decode_splits(int S, int H_kv, int total_tokens);
 bool decode_uses_mfma(const DecodeDims& d);

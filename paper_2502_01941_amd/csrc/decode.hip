@@ -70,8 +70,9 @@ template <typename T, int D, int G>
 __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     const T* __restrict__ k_prefill, const T* __restrict__ v_prefill,
     const int32_t* __restrict__ prefill_count, T* __restrict__ k_dec, T* __restrict__ v_dec,
-    const int32_t* __restrict__ slot_pos, int cap, int n_slots, int H, int H_kv, int n_splits,
-    int split_tokens, float scale_log2e, const T* __restrict__ q_new, const T* __restrict__ k_new,
+    const int32_t* __restrict__ slot_pos, int cap, int n_slots, int H, int H_kv, int n_group,
+    int n_splits, int split_tokens, float scale_log2e, const T* __restrict__ q_new,
+    const T* __restrict__ k_new,
     const T* __restrict__ v_new, float2* __restrict__ part_ml, float* __restrict__ part_o,
     float* __restrict__ z_dec, int32_t* __restrict__ new_slot_out) {
   constexpr int E = Vec16<T>::kElems;       // elements per 16-byte lane
@@ -105,8 +106,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     l[h] = 0.f;
 #pragma unroll
     for (int e = 0; e < E; ++e) o[h][e] = 0.f;
-    const uint4 raw = *reinterpret_cast<const uint4*>(
-        q_new + (static_cast<size_t>(s) * H + g * G + h) * D + lir * E);
+    // G is the group size rounded up to a power of two; heads past the real n_group are zero queries
+    uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+    if (h < n_group)
+      raw = *reinterpret_cast<const uint4*>(q_new + (static_cast<size_t>(s) * H + g * n_group + h) * D + lir * E);
     Vec16<T>::unpack(raw, q[h]);
   }
 
@@ -172,7 +175,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
         if (valid[u] && slot_of[u] >= 0 && lir == 0) {
 #pragma unroll
           for (int h = 0; h < G; ++h)
-            z_dec[(static_cast<size_t>(s) * H + g * G + h) * n_slots + slot_of[u]] = z[u][h];
+            if (h < n_group) z_dec[(static_cast<size_t>(s) * H + g * n_group + h) * n_slots + slot_of[u]] = z[u][h];
         }
       }
 #pragma unroll
@@ -247,7 +250,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
       L += s_l[w][h] * a;
       O += s_o[w][h][dd] * a;
     }
-    const size_t row = (static_cast<size_t>(s) * H + g * G + h) * n_splits + split;
+    if (h >= n_group) continue;
+    const size_t row = (static_cast<size_t>(s) * H + g * n_group + h) * n_splits + split;
     part_o[row * D + dd] = O;
     if (dd == 0) part_ml[row] = make_float2(M, L);
   }
@@ -415,10 +419,10 @@ static hipError_t launch_partial_g(const DecodeDims& d, const shotkv_decode_stat
   hipLaunchKernelGGL((decode_partial_kernel<T, D, GG>), grid, block, 0, s,                             \
                      static_cast<const T*>(st.k_prefill), static_cast<const T*>(st.v_prefill),         \
                      st.prefill_count, static_cast<T*>(st.k_dec), static_cast<T*>(st.v_dec),           \
-                     st.slot_pos, d.cap, d.n_slots, d.H, d.H_kv, d.n_splits, d.split_tokens, c,         \
+                     st.slot_pos, d.cap, d.n_slots, d.H, d.H_kv, d.G, d.n_splits, d.split_tokens, c,    \
                      static_cast<const T*>(q_new), static_cast<const T*>(k_new),                       \
                      static_cast<const T*>(v_new), w.part_ml, w.part_o, w.z_dec, w.new_slot)
-  switch (d.G) {
+  switch (padded_group(d.G)) {  // the kernel is instantiated for power-of-two groups and skips the padding
     case 1: SHOTKV_LAUNCH_DEC(1); break;
     case 2: SHOTKV_LAUNCH_DEC(2); break;
     case 4: SHOTKV_LAUNCH_DEC(4); break;

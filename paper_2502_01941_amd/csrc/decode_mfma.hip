@@ -56,8 +56,8 @@ template <int G>
 __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
     const bf16_t* __restrict__ k_prefill, const bf16_t* __restrict__ v_prefill,
     const int32_t* __restrict__ prefill_count, bf16_t* __restrict__ k_dec, bf16_t* __restrict__ v_dec,
-    const int32_t* __restrict__ slot_pos, int cap, int n_slots, int H, int H_kv, int n_splits,
-    int split_tokens, float scale_log2e, const bf16_t* __restrict__ q_new,
+    const int32_t* __restrict__ slot_pos, int cap, int n_slots, int H, int H_kv, int n_group,
+    int n_splits, int split_tokens, float scale_log2e, const bf16_t* __restrict__ q_new,
     const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new, float2* __restrict__ part_ml,
     float* __restrict__ part_o, float* __restrict__ z_dec, int32_t* __restrict__ new_slot_out) {
   const int split = blockIdx.x, g = blockIdx.y, s = blockIdx.z;
@@ -70,7 +70,9 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
   __shared__ int s_red[kWaves];
   __shared__ int s_sp[kMaxRange];  // slot map of the decode slots inside this workgroup's range
 
-  const size_t head0 = static_cast<size_t>(s) * H + static_cast<size_t>(g) * G;
+  // G is the group size rounded up to a power of two; heads past the real n_group are zero queries
+  // whose results are never written
+  const size_t head0 = static_cast<size_t>(s) * H + static_cast<size_t>(g) * n_group;
   // Query operands first: these loads and the one of the row count below are in flight together.
   const int i16 = lane & 15, ksl = lane >> 4;  // A row / B column, and k-slice (8 elements) of the lane
   const int tau = i16 >> 2, piece = i16 & 3;   // as A row; as B/C column: piece i16 >> 2, head i16 & 3
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
   for (int m = 0; m < kHeadSets; ++m) {
     u32x4 raw = {0u, 0u, 0u, 0u};
     const int hq = (i16 & 3) + 4 * m;
-    if (hq < G) raw = *reinterpret_cast<const u32x4*>(q_new + (head0 + hq) * kD + 32 * (i16 >> 2) + 8 * ksl);
+    if (hq < n_group) raw = *reinterpret_cast<const u32x4*>(q_new + (head0 + hq) * kD + 32 * (i16 >> 2) + 8 * ksl);
     bq[m] = __builtin_bit_cast(bf16x8, raw);
   }
   const int32_t* sp = slot_pos + static_cast<size_t>(s) * n_slots;
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
 
     // ---- between the passes: mask, maximum, weights and their sum; one wave per query head, so
     //      only wave-level reductions and no workgroup barrier in between ----------------------------
-    for (int h = wave; h < G; h += kWaves) {
+    for (int h = wave; h < n_group; h += kWaves) {
       float mx = -INFINITY;
       for (int tt = lane; tt < T; tt += kWave) {
         float z = zbuf[tt][h];
@@ -224,7 +226,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
         bool any = false;
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) {
-          p[u][hh] = inside ? zbuf[ttc][hh] : 0.f;
+          p[u][hh] = (inside && hh < n_group) ? zbuf[ttc][hh] : 0.f;  // padding heads carry no weight
           any = any || p[u][hh] != 0.f;
         }
         const int t = t_begin + ttc;
@@ -266,6 +268,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
   __syncthreads();
   for (int idx = tid; idx < G * kD; idx += kThreads) {
     const int hh = idx / kD, dd = idx % kD;
+    if (hh >= n_group) continue;
     float acc = 0.f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) acc += s_o[w][hh][dd];
@@ -291,10 +294,10 @@ hipError_t launch_decode_partial_mfma(const DecodeDims& d, const shotkv_decode_s
   hipLaunchKernelGGL(decode_partial_mfma_kernel<GG>, grid, block, 0, s,                                 \
                      static_cast<const bf16_t*>(st.k_prefill), static_cast<const bf16_t*>(st.v_prefill), \
                      st.prefill_count, static_cast<bf16_t*>(st.k_dec), static_cast<bf16_t*>(st.v_dec),   \
-                     st.slot_pos, d.cap, d.n_slots, d.H, d.H_kv, d.n_splits, d.split_tokens, c,          \
+                     st.slot_pos, d.cap, d.n_slots, d.H, d.H_kv, d.G, d.n_splits, d.split_tokens, c,     \
                      static_cast<const bf16_t*>(q_new), static_cast<const bf16_t*>(k_new),               \
                      static_cast<const bf16_t*>(v_new), w.part_ml, w.part_o, w.z_dec, w.new_slot)
-  switch (d.G) {
+  switch (padded_group(d.G)) {
     case 1: SHOTKV_LAUNCH_DEC(1); break;
     case 2: SHOTKV_LAUNCH_DEC(2); break;
     case 4: SHOTKV_LAUNCH_DEC(4); break;

@@ -167,14 +167,15 @@ struct PairShape {
   static constexpr int kNQW = NQB / kWaves;           // query blocks per wave
   static constexpr int kLoads = kGroupsPerBlock / kWaves;  // load instructions per wave per block
   static constexpr int kThreads = kWaves * kWave;
-  static constexpr int kMinWavesPerSimd = kWaves > 1 ? SHOTKV_SCORE_WAVES_PER_SIMD : 1;  // single-wave groups are LDS-limited
+  // single-wave groups are LDS-limited; four query blocks per wave need the 256-register budget
+  static constexpr int kMinWavesPerSimd = kWaves == 1 ? 1 : (kNQW > 2 ? 2 : SHOTKV_SCORE_WAVES_PER_SIMD);
 };
 
 template <int NQB>
 __global__ __launch_bounds__(PairShape<NQB>::kThreads, PairShape<NQB>::kMinWavesPerSimd) void
 score_partials_mfma_kernel(
     const bf16_t* __restrict__ q_obs, const bf16_t* __restrict__ k, int n_tokens, int H, int H_kv, int W,
-    float c, const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ chunk_start,
+    int n_rows, float c, const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ chunk_start,
     const int32_t* __restrict__ chunk_len, int max_c, int chunks_per_group,
     float* __restrict__ partial, float* __restrict__ group_stat) {
   typedef PairShape<NQB> S;
@@ -200,13 +201,20 @@ score_partials_mfma_kernel(
   const int qb0 = wave * NQW;
 
   // B operands: query row (qb0+q)*32 + lane%32, head-dim slice 16*ks + 8*(lane/32) .. +8
+  // Query rows past n_rows = G*W (a row count that is not one of 32/64/128/256) are zero operands; their
+  // statistics are written as -inf, so they carry no weight further down.
   bf16x8 bq[NQW][8];
 #pragma unroll
-  for (int q = 0; q < NQW; ++q)
+  for (int q = 0; q < NQW; ++q) {
+    const int qi = (qb0 + q) * 32 + (lane & 31);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-      bq[q][ks] = *reinterpret_cast<const bf16x8*>(q_rows + ((qb0 + q) * 32 + (lane & 31)) * kD + ks * 16 +
-                                                   (lane >> 5) * 8);
+    for (int ks = 0; ks < 8; ++ks) {
+      typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+      u32x4 raw = {0u, 0u, 0u, 0u};
+      if (qi < n_rows) raw = *reinterpret_cast<const u32x4*>(q_rows + qi * kD + ks * 16 + (lane >> 5) * 8);
+      bq[q][ks] = __builtin_bit_cast(bf16x8, raw);
+    }
+  }
   // the query loads must have landed before the streaming loop starts: inside the loop the only
   // vector-memory loads are the block loads, whose completion is tracked by hand
 #pragma unroll
@@ -231,7 +239,11 @@ score_partials_mfma_kernel(
   auto flush = [&]() {
     float* dst = out + static_cast<size_t>(pend_c) * H_kv * R + (lane & 31) * NQB + qb0;
     if (lane < 32) {
-      if (NQW == 2) *reinterpret_cast<float2*>(dst) = make_float2(pend[0], pend[NQW - 1]);
+#pragma unroll
+      for (int q = 0; q < NQW; ++q)
+        if ((qb0 + q) * 32 + lane >= n_rows) pend[q] = -INFINITY;
+      if (NQW == 4) *reinterpret_cast<float4*>(dst) = make_float4(pend[0], pend[1 % NQW], pend[2 % NQW], pend[3 % NQW]);
+      else if (NQW == 2) *reinterpret_cast<float2*>(dst) = make_float2(pend[0], pend[NQW - 1]);
       else dst[0] = pend[0];
     }
     pend_c = -1;
@@ -336,7 +348,9 @@ score_partials_mfma_kernel(
     float* dst = group_stat + ((static_cast<size_t>(p) * H_kv + g) * gridDim.x + blockIdx.x) * R +
                  (lane & 31) * NQB + qb0;
 #pragma unroll
-    for (int q = 0; q < NQW; ++q) dst[q] = (l_grp[q] > 0.f) ? m_run[q] + __builtin_amdgcn_logf(l_grp[q]) : -INFINITY;
+    for (int q = 0; q < NQW; ++q)
+      dst[q] = (l_grp[q] > 0.f && (qb0 + q) * 32 + lane < n_rows) ? m_run[q] + __builtin_amdgcn_logf(l_grp[q])
+                                                                 : -INFINITY;
   }
 }
 
@@ -357,7 +371,7 @@ int score_group_chunks(int P, int H_kv, int max_c) {
 }
 
 bool score_uses_mfma(const PrefillDims& d) {
-  return d.dtype == SHOTKV_BF16 && d.D == kD && (d.R == 32 || d.R == 64 || d.R == 128) &&
+  return d.dtype == SHOTKV_BF16 && d.D == kD && d.R_rows <= 256 &&
          static_cast<long>(d.n_tokens) * kRowBytes < (1L << 32);
 }
 
@@ -370,12 +384,13 @@ hipError_t launch_score_partials_mfma(const PrefillDims& d, const void* q_obs, c
 #define SHOTKV_LAUNCH_SCORE(NQB)                                                                      \
   hipLaunchKernelGGL(score_partials_mfma_kernel<NQB>, grid, dim3(PairShape<NQB>::kThreads), 0, s,     \
                      static_cast<const bf16_t*>(q_obs), static_cast<const bf16_t*>(k), d.n_tokens, d.H, \
-                     d.H_kv, d.W, c, w.n_chunks, w.chunk_start, w.chunk_len, w.max_c, cpg, w.partial,      \
+                     d.H_kv, d.W, d.R_rows, c, w.n_chunks, w.chunk_start, w.chunk_len, w.max_c, cpg, w.partial,      \
                      w.group_stat)
   switch (d.R / 32) {
     case 1: SHOTKV_LAUNCH_SCORE(1); break;
     case 2: SHOTKV_LAUNCH_SCORE(2); break;
     case 4: SHOTKV_LAUNCH_SCORE(4); break;
+    case 8: SHOTKV_LAUNCH_SCORE(8); break;
     default: return hipErrorInvalidValue;
   }
 #undef SHOTKV_LAUNCH_SCORE

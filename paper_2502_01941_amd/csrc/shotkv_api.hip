@@ -64,7 +64,7 @@ int check_config(const shotkv_config* cfg) {
   if (cfg->head_dim != 64 && cfg->head_dim != 128) return SHOTKV_E_SHAPE;
   if (cfg->n_kv_heads < 1 || cfg->n_q_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads) return SHOTKV_E_SHAPE;
   const int G = cfg->n_q_heads / cfg->n_kv_heads;
-  if (G != 1 && G != 2 && G != 4 && G != 8) return SHOTKV_E_SHAPE;
+  if (G > 8) return SHOTKV_E_SHAPE;
   if (cfg->n_q_heads > 64) return SHOTKV_E_SHAPE;
   if (cfg->select_mode != SHOTKV_SELECT_PREFIX && cfg->select_mode != SHOTKV_SELECT_FIRST_FIT)
     return SHOTKV_E_SHAPE;
@@ -83,7 +83,13 @@ int make_prefill_dims(const shotkv_config* cfg, int P, int n_tokens, int n_shots
   if (P < 1 || n_tokens < cfg->window || n_shots < 0 || n_shots > SHOTKV_MAX_SHOTS) return SHOTKV_E_SHAPE;
   d->P = P; d->n_tokens = n_tokens; d->n_shots = n_shots;
   d->H = cfg->n_q_heads; d->H_kv = cfg->n_kv_heads; d->G = G; d->D = cfg->head_dim;
-  d->W = cfg->window; d->R = G * cfg->window; d->dtype = cfg->dtype; d->sm_scale = cfg->sm_scale;
+  d->W = cfg->window; d->R_rows = G * cfg->window; d->R = d->R_rows; d->dtype = cfg->dtype;
+  d->sm_scale = cfg->sm_scale;
+  if (score_uses_mfma(*d)) {  // the matrix-core kernel works on 1, 2, 4 or 8 blocks of 32 query rows
+    int blocks = 1;
+    while (blocks * 32 < d->R_rows) blocks *= 2;
+    d->R = blocks * 32;
+  }
   d->select_mode = cfg->select_mode;
   d->share = 1;
   if (cfg->head_mode == SHOTKV_HEADS_PER_KV_HEAD) {

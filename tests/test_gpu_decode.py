@@ -193,3 +193,30 @@ def test_long_cache_many_splits(kv):
         _compare_step(state, 0, r, seq, near)
         assert r["evicted_pos"] >= 0
     assert not near
+
+
+@pytest.mark.parametrize("H,H_kv,D,dtype", [(28, 4, 128, torch.bfloat16), (40, 8, 128, torch.bfloat16),
+                                             (12, 4, 128, torch.bfloat16), (6, 2, 64, torch.float32)])
+def test_group_sizes_that_are_not_powers_of_two(kv, H, H_kv, D, dtype):
+    """G = 7, 5, 3: the kernels run on the next power of two and must neither read nor write the padding
+    heads.  Dead rows of the prefill cache hold NaN / Inf."""
+    shape = wl.DecodeShape("g", 2, H, H_kv, D, 500, 6, 0, dtype)
+    st = wl.decode_state(shape, "cuda", 5)
+    st["prefill_count"] = torch.tensor([500, 333], dtype=torch.int32, device="cuda")
+    st["k_prefill"][1, :, 333:] = float("nan")
+    st["v_prefill"][1, :, 333:] = float("inf")
+    state = _make_state(kv, shape, st)
+    seqs = [OracleSeq(st, s) for s in range(2)]
+    seqs[1].kp, seqs[1].vp = seqs[1].kp[:, :333].copy(), seqs[1].vp[:, :333].copy()
+    near = []
+    guard = torch.full_like(state.out, 12345.0)
+    for step in range(10):
+        q, kn, vn = wl.decode_inputs(shape, step, "cuda", 5)
+        state.out.copy_(guard)
+        kv.decode_step(state, step, q, kn, vn)
+        torch.cuda.synchronize()
+        assert torch.isfinite(state.out).all()
+        for s, seq in enumerate(seqs):
+            r = seq.step(shape.decode_budget, step, q[s], kn[s], vn[s], shape.sm_scale)
+            _compare_step(state, s, r, seq, near)
+    assert not near

@@ -82,6 +82,11 @@ def _ragged_problem(P, H, Hkv, D, W, N, dtype, seed, n_shots, prefix, tail_min):
     (8, 2, 128, 64, 600, torch.bfloat16, 4),      # the widest window, G=4 -> 256 rows (generic path)
     (64, 8, 128, 32, 450, torch.bfloat16, 3),     # the most query heads, G=8 -> 256 rows
     (4, 4, 128, 1, 200, torch.bfloat16, 3),       # a single window query
+    (28, 4, 128, 32, 1100, torch.bfloat16, 6),    # G=7 -> 224 rows, padded to 256 on the matrix-core path
+    (40, 8, 128, 32, 900, torch.bfloat16, 5),     # G=5 -> 160 rows
+    (12, 4, 128, 32, 800, torch.bfloat16, 5),     # G=3 -> 96 rows
+    (24, 4, 128, 20, 700, torch.bfloat16, 4),     # G=6, W=20 -> 120 rows
+    (6, 2, 64, 16, 500, torch.float32, 4),        # G=3 on the generic path
 ])
 def test_ragged_shapes(kv, H, Hkv, D, W, N, dtype, n_shots):
     P = 3
