@@ -242,9 +242,14 @@ score_partials_mfma_kernel(
 #pragma unroll
       for (int q = 0; q < NQW; ++q)
         if ((qb0 + q) * 32 + lane >= n_rows) pend[q] = -INFINITY;
-      if (NQW == 4) *reinterpret_cast<float4*>(dst) = make_float4(pend[0], pend[1 % NQW], pend[2 % NQW], pend[3 % NQW]);
-      else if (NQW == 2) *reinterpret_cast<float2*>(dst) = make_float2(pend[0], pend[NQW - 1]);
-      else dst[0] = pend[0];
+      if (NQW == 4) {
+        *reinterpret_cast<float4*>(dst) = make_float4(pend[0], pend[1 % NQW], pend[2 % NQW], pend[3 % NQW]);
+      } else if (NQW == 2) {
+        *reinterpret_cast<float2*>(dst) = make_float2(pend[0], pend[NQW - 1]);
+      } else {
+#pragma unroll
+        for (int q = 0; q < NQW; ++q) dst[q] = pend[q];
+      }
     }
     pend_c = -1;
   };
@@ -390,6 +395,7 @@ hipError_t launch_score_partials_mfma(const PrefillDims& d, const void* q_obs, c
     case 1: SHOTKV_LAUNCH_SCORE(1); break;
     case 2: SHOTKV_LAUNCH_SCORE(2); break;
     case 4: SHOTKV_LAUNCH_SCORE(4); break;
+    case 6: SHOTKV_LAUNCH_SCORE(6); break;
     case 8: SHOTKV_LAUNCH_SCORE(8); break;
     default: return hipErrorInvalidValue;
   }

@@ -85,9 +85,9 @@ int make_prefill_dims(const shotkv_config* cfg, int P, int n_tokens, int n_shots
   d->H = cfg->n_q_heads; d->H_kv = cfg->n_kv_heads; d->G = G; d->D = cfg->head_dim;
   d->W = cfg->window; d->R_rows = G * cfg->window; d->R = d->R_rows; d->dtype = cfg->dtype;
   d->sm_scale = cfg->sm_scale;
-  if (score_uses_mfma(*d)) {  // the matrix-core kernel works on 1, 2, 4 or 8 blocks of 32 query rows
-    int blocks = 1;
-    while (blocks * 32 < d->R_rows) blocks *= 2;
+  if (score_uses_mfma(*d)) {  // the matrix-core kernel works on 1, 2, 4, 6 or 8 blocks of 32 query rows
+    const int need = ceil_div(d->R_rows, 32);
+    const int blocks = need <= 2 ? need : need <= 4 ? 4 : need <= 6 ? 6 : 8;
     d->R = blocks * 32;
   }
   d->select_mode = cfg->select_mode;

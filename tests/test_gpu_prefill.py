@@ -87,6 +87,7 @@ def _ragged_problem(P, H, Hkv, D, W, N, dtype, seed, n_shots, prefix, tail_min):
     (12, 4, 128, 32, 800, torch.bfloat16, 5),     # G=3 -> 96 rows
     (24, 4, 128, 20, 700, torch.bfloat16, 4),     # G=6, W=20 -> 120 rows
     (6, 2, 64, 16, 500, torch.float32, 4),        # G=3 on the generic path
+    (24, 4, 128, 32, 900, torch.bfloat16, 5),     # G=6 -> 192 rows, six blocks
 ])
 def test_ragged_shapes(kv, H, Hkv, D, W, N, dtype, n_shots):
     P = 3
