@@ -26,7 +26,7 @@ HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
 # `rocprofv3 --pmc` runs of this file, see profiles/score_partials_mfma_model32k_counters.md).  Valid only
 # for the kernel source it was measured on: reported as null once that file's hash differs.
 SCORE_KERNEL_SOURCE = os.path.join(ROOT, "paper_2502_01941_amd", "csrc", "prefill_score_mfma.hip")
-MEASURED_TRAFFIC = {"model32k": {"sha256": "d869a48541943e97afbb0c995a8380dacbbde0822ce0d08d2c2c9e03321e2db9", "bytes": 8.98e9}}
+MEASURED_TRAFFIC = {"model32k": {"sha256": "7ec6078df68c29390258b8c9c566c7b887694dc6e0a0eab4db0d3d19d1f15929", "bytes": 8.98e9}}
 
 
 def _measured_traffic(workload):
