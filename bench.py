@@ -209,14 +209,25 @@ def main():
                             "algorithmic_gbps": dbytes / us / 1e3, "hbm_frac": dbytes / us / 1e3 / HBM_PEAK_GBPS,
                             "steps": args.decode_steps}
 
+    # What a plain streaming kernel reaches on this machine: torch's elementwise int32 x + 1 over 1 GiB (reads
+    # 1 GiB, writes 1 GiB).  Context for the roofline fractions, and with --calibrate-copy the kernel of
+    # known traffic that the profiler's byte counters are scaled by.
+    src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.add(src, 1, out=dst)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(10):
+        torch.add(src, 1, out=dst)
+    stop.record()
+    torch.cuda.synchronize()
+    copy_gbps = 10 * 2 * (1 << 30) / (start.elapsed_time(stop) * 1e-3) / 1e9
+    result["achievable"] = {"copy_read_plus_write_gbps": copy_gbps, "kernel": "torch int32 add-scalar, 1 GiB in, 1 GiB out"}
+    result["roofline"]["frac_of_copy"] = result["roofline"]["achieved"] / copy_gbps
     if args.calibrate_copy:
-        # a plain elementwise kernel that reads 1 GiB and writes 1 GiB (int32 x + 1), easy to find by name
-        src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.add(src, 1, out=dst)
-        torch.cuda.synchronize()
         result["calibration_kernel"] = {"op": "int32 add-scalar", "read_bytes": 1 << 30, "write_bytes": 1 << 30}
+    del src, dst
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(shape, args.cpu_problems, seed)
