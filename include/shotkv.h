@@ -164,6 +164,9 @@ SHOTKV_API int shotkv_select_and_compact(const shotkv_config* cfg, int32_t P, in
  * once and remains fixed", Section 5.1).  Generated tokens live in a pool of n_slots slots per
  * sequence; slot_pos holds the generated-token index in each slot, -1 when free (initialise to -1).
  * n_slots must be >= decode_budget + 1 unless the caller guarantees fewer steps than n_slots.
+ * Rows of the prefill cache past prefill_count may hold anything: they may be fetched but never
+ * influence a result.  decode_budget may change from step to step, e.g. ceil(r_d * (step_index + 1))
+ * for the ratio form of Eq. 8.
  * In per-KV-head mode prefill_count is [S][H_kv] and slot_pos [S][H_kv][n_slots]: every KV head has
  * its own live row count and its own slot map.
  */
