@@ -230,7 +230,9 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
           any = any || p[u][hh] != 0.f;
         }
         const int t = t_begin + ttc;
-        const bool is_new = any && t >= cap && (t - cap) == new_slot;
+        // the slot taking the new token: its value row is appended whatever weight the token got
+        // (a weight that underflows to zero must not leave a stale row behind for later steps)
+        const bool is_new = inside && t >= cap && (t - cap) == new_slot;
         const bf16_t* vr = v_new + new_off;
         if (any && !is_new) vr = (t < cap) ? v_prefill + (plane_p + t) * kD : v_dec + (plane_d + (t - cap)) * kD;
         raw[u] = *reinterpret_cast<const u32x4*>(vr + lir * 8);

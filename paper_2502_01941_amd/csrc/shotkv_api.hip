@@ -259,7 +259,7 @@ static int make_decode_dims(const shotkv_config* cfg, int S, int cap, int n_slot
   d->D = cfg->head_dim; d->dtype = cfg->dtype; d->cap = cap; d->n_slots = n_slots;
   d->sm_scale = cfg->sm_scale;
   const int total = cap + n_slots;
-  d->n_splits = decode_splits(S, d->H_kv, total);
+  d->n_splits = decode_splits(d->S, d->H_kv, total);  // pairs after the per-KV-head rewrite
   d->split_tokens = ceil_div(total, d->n_splits);
   return SHOTKV_OK;
 }

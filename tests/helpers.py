@@ -48,15 +48,27 @@ def check_selection_valid(sel, kept, pos, off, n_tokens, budget):
     np.testing.assert_array_equal(pos, np.concatenate(expect))
 
 
+def replay_selection(gpu_scores, off, n_tokens, budget, mode):
+    """The oracle's ranked walk run on the scores a device produced: (keep mask, kept positions).
+    None when the tokens outside the shots alone exceed the budget."""
+    off = np.asarray(off, dtype=np.int64)
+    shot_budget = int(budget) - int(off[0]) - int(n_tokens - off[-1])
+    if shot_budget < 0:
+        return None
+    keep = orc.select_shots(np.asarray(gpu_scores), np.diff(off), shot_budget, mode)
+    return keep, orc.kept_positions_from_mask(keep, off, n_tokens)
+
+
 def check_prefill_problem(res, p, q, k, v, off, budget, cap, sm_scale, mode=orc.SELECT_PREFIX,
                           report=None, ref=None):
     """Compare problem p of a device PrefillResult with the oracle, element by element.
 
-    Scores within SCORE_RTOL.  Selection, kept positions and compacted K/V bit-exact against the oracle
-    whenever the oracle's decision margin is at least MARGIN_EXACT (with exact arithmetic the result is
-    unique; a closer call may legitimately flip in fp32, is then only checked for validity and is
-    recorded in `report`).  The compacted rows must always be bit-exact copies of the rows named by
-    kept_positions.  `ref` passes in an oracle result computed elsewhere for the same inputs.
+    (i) scores within SCORE_RTOL; (ii) always: the device's selection, kept positions and compacted K/V
+    are bit-exact what the oracle's ranked walk gives on the device's own scores; (iii) the same against
+    the oracle end to end whenever the oracle's decision margin is at least MARGIN_EXACT (with exact
+    arithmetic the result is unique; a closer call may legitimately flip in fp32 and is recorded in
+    `report` as (problem, margin, agrees)).  `ref` passes in an oracle result computed elsewhere for the
+    same inputs.
     """
     budget = min(int(budget), cap)
     if ref is None:
@@ -75,15 +87,20 @@ def check_prefill_problem(res, p, q, k, v, off, budget, cap, sm_scale, mode=orc.
         return ref
     pos = res.kept_positions[p, :kept].cpu().numpy()
     check_selection_valid(sel, kept, pos, off, k.shape[1], budget)
-    idx = torch.from_numpy(pos).long().to(k.device)
-    np.testing.assert_array_equal(bits(res.k_out[p, :, :kept]), bits(k[:, idx]))
-    np.testing.assert_array_equal(bits(res.v_out[p, :, :kept]), bits(v[:, idx]))
+    # (ii) the selection rule itself, independent of score rounding
+    keep_replay, pos_replay = replay_selection(gpu_scores, off, k.shape[1], budget, mode)
+    assert sel.tolist() == keep_replay.tolist(), f"problem {p}: selection differs from the walk on its own scores"
+    np.testing.assert_array_equal(pos, pos_replay)
+    k_host, v_host = to_np(k), to_np(v)
+    np.testing.assert_array_equal(to_np(res.k_out[p, :, :kept]), k_host[:, pos_replay])
+    np.testing.assert_array_equal(to_np(res.v_out[p, :, :kept]), v_host[:, pos_replay])
+    agrees = sel.tolist() == ref["selected"].tolist()
     if ref["margin"] >= MARGIN_EXACT:
-        assert sel.tolist() == ref["selected"].tolist(), f"problem {p}: margin {ref['margin']}"
+        assert agrees, f"problem {p}: margin {ref['margin']}"
         assert kept == ref["kept_count"]
         np.testing.assert_array_equal(pos, ref["kept_positions"])
         np.testing.assert_array_equal(to_np(res.k_out[p, :, :kept]), ref["k_out"].astype(np.float32))
         np.testing.assert_array_equal(to_np(res.v_out[p, :, :kept]), ref["v_out"].astype(np.float32))
     elif report is not None:
-        report.append((p, ref["margin"], sel.tolist() == ref["selected"].tolist()))
+        report.append((p, ref["margin"], agrees))
     return ref

@@ -63,6 +63,9 @@ def _compare_step(state, s, r, seq, near_ties):
         seq.slot_pos[alt_slot] = -1
         near_ties.append((s, ev))
     np.testing.assert_array_equal(state.slot_pos[s].cpu().numpy(), seq.slot_pos)
+    # the slot pool itself: the appended K/V rows are bit-exact copies, nothing else is touched
+    np.testing.assert_array_equal(to_np(state.k_dec[s]), seq.kd)
+    np.testing.assert_array_equal(to_np(state.v_dec[s]), seq.vd)
 
 
 def test_tiny_free_running_320_steps(kv):
@@ -87,18 +90,21 @@ def test_tiny_free_running_320_steps(kv):
     np.testing.assert_array_equal(to_np(st["v_dec"][0]), seq.vd)
 
 
-def test_decode4k_bf16_lockstep(kv):
-    """The long-generation shape (16 sequences, 4096-token prefill cache, budget 1024) around the point
-    where eviction starts: the state holds 1000 generated tokens, 64 more steps follow; two sequences
-    are followed by the oracle at every step."""
+@pytest.mark.parametrize("group", range(4))
+def test_decode4k_bf16_lockstep(kv, group):
+    """The long-generation shape (16 sequences, 4096-token prefill cache, budget 1024) from a partly
+    filled pool through the point where eviction starts and on into the steady state: the state holds
+    768 generated tokens, 512 more steps follow (256 that fill the pool, 256 that evict every step).
+    All 16 sequences are decoded in every launch; the four parametrisations follow four sequences each
+    with the oracle at every step, so together every sequence is followed."""
     shape = wl.DECODE4K
-    resident = 1000
+    resident, steps = 768, 512
     st = wl.decode_state(shape, "cuda", resident=resident)
     state = _make_state(kv, shape, st)
-    tracked = {0: OracleSeq(st, 0), 11: OracleSeq(st, 11)}
+    tracked = {s: OracleSeq(st, s) for s in range(group, shape.n_seqs, 4)}
     vsum_before = st["v_prefill"].float().sum().item()
     near = []
-    for step in range(resident, resident + 64):
+    for step in range(resident, resident + steps):
         q, kn, vn = wl.decode_inputs(shape, step, "cuda")
         kv.decode_step(state, step, q, kn, vn)
         torch.cuda.synchronize()
@@ -110,7 +116,9 @@ def test_decode4k_bf16_lockstep(kv):
     counts = (state.slot_pos >= 0).sum(dim=1).cpu().tolist()
     assert counts == [shape.decode_budget] * shape.n_seqs
     assert st["v_prefill"].float().sum().item() == vsum_before
-    assert len(near) <= 2, near
+    # 4 x 256 evictions among ~1000 candidates each: a pair of lowest scores within 1e-6 is rare
+    print(f"\n[decode4k group {group}] near-tie evictions followed: {near}")
+    assert len(near) <= 4, near
 
 
 def test_partial_prefill_and_unbounded_budget(kv):
@@ -219,4 +227,34 @@ def test_group_sizes_that_are_not_powers_of_two(kv, H, H_kv, D, dtype):
         for s, seq in enumerate(seqs):
             r = seq.step(shape.decode_budget, step, q[s], kn[s], vn[s], shape.sm_scale)
             _compare_step(state, s, r, seq, near)
+    assert not near
+
+
+@pytest.mark.parametrize("H,H_kv", [(32, 8), (8, 8), (16, 2)])
+def test_new_token_without_weight_is_still_appended(kv, H, H_kv):
+    """Algorithm 1 phase 2 appends the generated token's K/V unconditionally.  Here the new key is
+    opposed to every query of its group by about 180 nats, so its weight is exactly zero in fp32 at the
+    step that appends it; the value row must land in the pool all the same, because later steps (with
+    ordinary queries) give that token real weight.  Pool contents are compared bit for bit after every
+    step."""
+    shape = wl.DecodeShape("noweight", 2, H, H_kv, 128, 300, 64, 0, torch.bfloat16)
+    st = wl.decode_state(shape, "cuda", 9, n_slots=12)
+    st["v_dec"].fill_(7.0)                       # a stale row would be visible in the output
+    state = _make_state(kv, shape, st)
+    seqs = [OracleSeq(st, s) for s in range(2)]
+    near = []
+    for step in range(6):
+        q, kn, vn = wl.decode_inputs(shape, step, "cuda", 9)
+        if step in (0, 2, 3):
+            q = torch.full_like(q, 4.0)
+            kn = torch.full_like(kn, -4.0)
+        kv.decode_step(state, step, q, kn, vn)
+        torch.cuda.synchronize()
+        for s, seq in enumerate(seqs):
+            r = seq.step(shape.decode_budget, step, q[s], kn[s], vn[s], shape.sm_scale)
+            if step in (0, 2, 3):
+                assert float(state.token_scores[s, r["new_slot"]].item()) == 0.0   # the case is really hit
+            _compare_step(state, s, r, seq, near)
+            slot = r["new_slot"]
+            assert torch.equal(state.v_dec[s, :, slot], vn[s]) and torch.equal(state.k_dec[s, :, slot], kn[s])
     assert not near

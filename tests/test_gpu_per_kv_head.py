@@ -110,7 +110,9 @@ def test_decode_per_kv_head_lockstep(kv, dtype, D, H, H_kv):
             seqs[(s, g)] = OracleSeq(one, s)
     view = types.SimpleNamespace(status=state.status.view(-1), out=state.out.view(S * H_kv, G, D),
                                  token_scores=state.token_scores.view(S * H_kv, n_slots),
-                                 evicted_pos=state.evicted_pos.view(-1), slot_pos=slot_pos.view(S * H_kv, n_slots))
+                                 evicted_pos=state.evicted_pos.view(-1), slot_pos=slot_pos.view(S * H_kv, n_slots),
+                                 k_dec=st["k_dec"].view(S * H_kv, 1, n_slots, D),
+                                 v_dec=st["v_dec"].view(S * H_kv, 1, n_slots, D))
     near, evicted = [], set()
     for step in range(steps):
         q, kn, vn = wl.decode_inputs(shape, step, "cuda", 7)
