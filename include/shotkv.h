@@ -62,7 +62,8 @@ enum {
   SHOTKV_E_SHAPE = -2,     /* unsupported or inconsistent shape / dtype / mode   */
   SHOTKV_E_WORKSPACE = -3, /* workspace_bytes smaller than *_workspace_bytes()   */
   SHOTKV_E_ALIGN = -4,     /* a tensor pointer is not 16-byte aligned            */
-  SHOTKV_E_LAUNCH = -5     /* the HIP runtime refused a launch                   */
+  SHOTKV_E_LAUNCH = -5,    /* the HIP runtime refused a launch                   */
+  SHOTKV_E_SCRATCH = -6    /* shotkv_decode_step_static: needs more than SHOTKV_STATIC_SCRATCH_BYTES */
 };
 
 /* Per-problem device-side status words. */
@@ -207,6 +208,27 @@ SHOTKV_API int shotkv_decode_step(const shotkv_config* cfg, int32_t S, const sho
                        int32_t step_index, const void* q_new, const void* k_new, const void* v_new,
                        float* out, float* token_scores, int32_t* evicted_pos, int32_t* status,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * shotkv_decode_step without a workspace argument, for callers that cannot allocate device memory:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels,
+ * same arguments, same results as shotkv_decode_step; the workspace is a buffer of
+ * SHOTKV_STATIC_SCRATCH_BYTES that is part of the library's device image (one copy per GPU, held until
+ * the process ends).  The call allocates and frees nothing and creates no objects.  The first call on
+ * a GPU looks up the buffer's address (make that call outside a graph capture).
+ *
+ * Limit: returns SHOTKV_E_SCRATCH, and enqueues nothing, when shotkv_decode_workspace_bytes(cfg, S,
+ * st->cap, st->n_slots) exceeds SHOTKV_STATIC_SCRATCH_BYTES (8 MiB holds e.g. 16 sequences with 32
+ * query heads, head_dim 128, a 4096-row prefill cache and 1025 slots).
+ * All calls on one GPU share the buffer, whatever their stream: calls that may overlap in time race
+ * with each other; order them on one stream or with events.  The buffer keeps the last call's
+ * contents; a step reads nothing from it that it has not written itself.
+ */
+#define SHOTKV_STATIC_SCRATCH_BYTES (8u << 20)
+SHOTKV_API int shotkv_decode_step_static(const shotkv_config* cfg, int32_t S, const shotkv_decode_state* st,
+                              int32_t step_index, const void* q_new, const void* k_new, const void* v_new,
+                              float* out, float* token_scores, int32_t* evicted_pos, int32_t* status,
+                              void* stream);
 
 #ifdef __cplusplus
 }

@@ -2,10 +2,33 @@
 // Every entry point only enqueues work on the caller's stream.
 #include "common.hpp"
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
+// Scratch memory of shotkv_decode_step_static: one copy per GPU the library runs on, held until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[SHOTKV_STATIC_SCRATCH_BYTES];
+
 namespace shotkv {
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, once known
+
+// Device address of the scratch array on the current GPU; looked up once per device.
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SHOTKV_E_LAUNCH;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SHOTKV_E_LAUNCH;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // a racing thread stores the same value
+  }
+  *out = ptr;
+  return SHOTKV_OK;
+}
+}  // namespace
 
 // ---- per-kernel timing ---------------------------------------------------------------------------
 
@@ -126,6 +149,7 @@ const char* shotkv_strerror(int code) {
     case SHOTKV_E_WORKSPACE: return "workspace too small";
     case SHOTKV_E_ALIGN: return "tensor pointer not 16-byte aligned";
     case SHOTKV_E_LAUNCH: return "HIP launch failed";
+    case SHOTKV_E_SCRATCH: return "problem needs more scratch than the static buffer holds";
     default: return "unknown shotkv error";
   }
 }
@@ -294,6 +318,24 @@ int shotkv_decode_step(const shotkv_config* cfg, int32_t S, const shotkv_decode_
   hipError_t e = launch_decode_partial(d, *st, q_new, k_new, v_new, w, s);
   if (e == hipSuccess) e = launch_decode_finish(d, *st, out, token_scores, evicted_pos, status, w, s);
   return from_hip(e);
+}
+
+int shotkv_decode_step_static(const shotkv_config* cfg, int32_t S, const shotkv_decode_state* st,
+                              int32_t step_index, const void* q_new, const void* k_new, const void* v_new,
+                              float* out, float* token_scores, int32_t* evicted_pos, int32_t* status,
+                              void* stream) {
+  if (!st) return SHOTKV_E_NULL;
+  DecodeDims d;
+  const int rc = make_decode_dims(cfg, S, st->cap, st->n_slots, &d);
+  if (rc != SHOTKV_OK) return rc;
+  const size_t need = carve_decode(nullptr, d.S, d.H, d.H_kv, d.D, d.n_slots, d.n_splits).bytes;
+  if (need > static_cast<size_t>(SHOTKV_STATIC_SCRATCH_BYTES)) return SHOTKV_E_SCRATCH;
+  void* ptr = nullptr;
+  const int rs = static_scratch(&ptr);
+  if (rs != SHOTKV_OK) return rs;
+  // nothing in the decode workspace has to start at zero: every word a step reads it has written itself
+  return shotkv_decode_step(cfg, S, st, step_index, q_new, k_new, v_new, out, token_scores, evicted_pos,
+                            status, ptr, need, stream);
 }
 
 }  // extern "C"

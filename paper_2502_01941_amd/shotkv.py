@@ -21,11 +21,14 @@ SELECT_PREFIX, SELECT_FIRST_FIT = 0, 1
 HEADS_PER_LAYER, HEADS_PER_KV_HEAD = 0, 1
 ST_OK, ST_BAD_OFFSETS, ST_BUDGET_TOO_SMALL, ST_NO_FREE_SLOT = 0, -1, -2, -3
 INT32_MAX = 2 ** 31 - 1
+E_SCRATCH = -6
+STATIC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = (
     "shotkv_strerror", "shotkv_abi_version", "shotkv_prefill_workspace_bytes",
     "shotkv_prefill_compress", "shotkv_prefill_scores", "shotkv_select_and_compact",
-    "shotkv_decode_workspace_bytes", "shotkv_decode_step", "shotkv_profile_enable",
+    "shotkv_decode_workspace_bytes", "shotkv_decode_step", "shotkv_decode_step_static",
+    "shotkv_profile_enable",
     "shotkv_profile_read",
 )
 
@@ -83,6 +86,9 @@ def load_library() -> ctypes.CDLL:
     lib.shotkv_decode_step.restype = ctypes.c_int
     lib.shotkv_decode_step.argtypes = [cfgp, i32, ctypes.POINTER(_DecodeState), i32, vp, vp, vp, vp, vp,
                                        vp, vp, vp, sz, vp]
+    lib.shotkv_decode_step_static.restype = ctypes.c_int
+    lib.shotkv_decode_step_static.argtypes = [cfgp, i32, ctypes.POINTER(_DecodeState), i32, vp, vp, vp, vp, vp,
+                                              vp, vp, vp]
     lib.shotkv_profile_enable.restype = ctypes.c_int
     lib.shotkv_profile_enable.argtypes = [ctypes.c_int]
     lib.shotkv_profile_read.restype = ctypes.c_int
@@ -294,6 +300,20 @@ def decode_step(state: DecodeState, step_index: int, q_new, k_new, v_new, want_s
         _ptr(state.token_scores) if want_scores else None, _ptr(state.evicted_pos), _ptr(state.status),
         _ptr(state.workspace), state.workspace.numel(), _stream())
     _check(rc, "shotkv_decode_step")
+    return state.out
+
+
+def decode_step_static(state: DecodeState, step_index: int, q_new, k_new, v_new, want_scores=True):
+    """shotkv_decode_step_static: the same step on the library's own static scratch buffer (state.workspace
+    is not used).  Raises ShotKVError (SHOTKV_E_SCRATCH) when the shape needs more than STATIC_SCRATCH_BYTES."""
+    S, H, H_kv, D = state.S, state.H, state.H_kv, state.D
+    rc = load_library().shotkv_decode_step_static(
+        ctypes.byref(state.cfg), S, ctypes.byref(state.c_state), int(step_index),
+        _ptr(q_new, state.dtype, (S, H, D), "q_new"), _ptr(k_new, state.dtype, (S, H_kv, D), "k_new"),
+        _ptr(v_new, state.dtype, (S, H_kv, D), "v_new"), _ptr(state.out),
+        _ptr(state.token_scores) if want_scores else None, _ptr(state.evicted_pos), _ptr(state.status),
+        _stream())
+    _check(rc, "shotkv_decode_step_static")
     return state.out
 
 
