@@ -77,30 +77,33 @@ struct PrefillWorkspace {
   // softmax partial per (problem, chunk, kv head, row): log2 of the chunk's sum of exponentials
   // (-inf for a row that sees none of the chunk's keys)
   float*   partial;       // [P][maxC][H_kv][R]
-  // the same statistic over each run of group_chunks consecutive chunks, which is what the row
-  // denominators are built from; with group_chunks == 1 it is the partial array itself
+  // matrix-core score path: a score workgroup ("group") takes the chunks that start inside one slice
+  // of group_keys keys; group g of a problem owns chunks [group_first[g], group_first[g + 1])
+  int32_t* group_first;   // [P][n_groups + 1]
+  // the same statistic over all chunks of a group, which is what the row denominators are built
+  // from; on the generic path (one chunk per workgroup) it is the partial array itself
   float*   group_stat;    // [P][H_kv][n_groups][R]
   float*   row_stat;      // [P][H_kv][R]  log2 of the row's sum of exponentials over all chunks
   float*   chunk_mass;    // [P][maxC]
   float*   scores;        // [P][n_shots]
   int32_t  max_c;
   int32_t  chunk_keys;
-  int32_t  group_chunks;  // chunks per score workgroup
-  int32_t  n_groups;      // ceil(max_c / group_chunks)
+  int32_t  group_keys;    // keys per slice of the key axis, 0 on the generic path
+  int32_t  n_groups;      // ceil(n_tokens / group_keys); max_c on the generic path
   size_t   bytes;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-int score_group_chunks(int P, int H_kv, int max_c);  // chunks per workgroup of the matrix-core score kernel
+int score_group_keys(int P, int H_kv, int n_tokens);  // keys per workgroup of the matrix-core score kernel
 
 inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_tokens, int n_shots,
                                       bool mfma_score) {
   PrefillWorkspace w{};
   w.chunk_keys = mfma_score ? kChunkKeys : kChunkKeysGeneric;
   w.max_c = max_chunks(n_tokens, n_shots, w.chunk_keys);
-  w.group_chunks = mfma_score ? score_group_chunks(P, H_kv, w.max_c) : 1;
-  w.n_groups = ceil_div(w.max_c, w.group_chunks);
+  w.group_keys = mfma_score ? score_group_keys(P, H_kv, n_tokens) : 0;
+  w.n_groups = mfma_score ? ceil_div(n_tokens, w.group_keys) : w.max_c;
   size_t off = 0;
   char* b = static_cast<char*>(base);
   auto take = [&](size_t bytes) {
@@ -113,8 +116,9 @@ inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_
   w.chunk_start = reinterpret_cast<int32_t*>(take(P_ * C * 4));
   w.chunk_len = reinterpret_cast<int32_t*>(take(P_ * C * 4));
   w.seg_first = reinterpret_cast<int32_t*>(take(P_ * (S + 3) * 4));
+  w.group_first = mfma_score ? reinterpret_cast<int32_t*>(take(P_ * (w.n_groups + 1) * 4)) : nullptr;
   w.partial = reinterpret_cast<float*>(take(P_ * H_kv * C * R * 4));
-  w.group_stat = w.group_chunks > 1 ? reinterpret_cast<float*>(take(P_ * H_kv * w.n_groups * R * 4)) : w.partial;
+  w.group_stat = mfma_score ? reinterpret_cast<float*>(take(P_ * H_kv * w.n_groups * R * 4)) : w.partial;
   w.row_stat = reinterpret_cast<float*>(take(P_ * H_kv * R * 4));
   w.chunk_mass = reinterpret_cast<float*>(take(P_ * C * 4));
   w.scores = reinterpret_cast<float*>(take(P_ * S * 4 + 4));

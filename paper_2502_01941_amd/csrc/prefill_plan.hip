@@ -35,7 +35,8 @@ __device__ __forceinline__ int chunk_stride(int len, int nc) {
 __global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
     const int32_t* __restrict__ shot_offsets, int share, int n_shots, int n_tokens, int chunk_keys, int max_c,
     int32_t* __restrict__ status, int32_t* __restrict__ n_chunks, int32_t* __restrict__ chunk_start,
-    int32_t* __restrict__ chunk_len, int32_t* __restrict__ seg_first) {
+    int32_t* __restrict__ chunk_len, int32_t* __restrict__ seg_first, int group_keys, int n_groups,
+    int32_t* __restrict__ group_first) {
   const int p = blockIdx.x;
   const int tid = threadIdx.x;
   const int32_t* off = shot_offsets + static_cast<size_t>(p / share) * (n_shots + 1);
@@ -58,9 +59,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
   }
   if (local_bad) atomicOr(&bad, 1);
   __syncthreads();
+  int32_t* g_first = group_first ? group_first + static_cast<size_t>(p) * (n_groups + 1) : nullptr;
   if (bad) {
     if (tid == 0) { status[p] = SHOTKV_ST_BAD_OFFSETS; n_chunks[p] = 0; }
     for (int s = tid; s < n_shots + 3; s += kPlanThreads) s_first[s] = 0;
+    if (g_first)
+      for (int gi = tid; gi <= n_groups; gi += kPlanThreads) g_first[gi] = 0;
     return;
   }
   if (tid == 0) status[p] = SHOTKV_ST_OK;
@@ -101,6 +105,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
     s_first[n_seg] = carry;
     n_chunks[p] = carry;
   }
+  if (g_first) {
+    // Group g of the score pass owns the chunks that start in key slice [g * group_keys, (g + 1) *
+    // group_keys): group_first[g] = first chunk starting at or after the slice's first key.  Chunk
+    // starts increase, so chunk c opens every group after its predecessor's up to its own.
+    const int nc = carry;  // final since the barrier that ended the loop above
+    for (int c = tid; c <= nc; c += kPlanThreads) {
+      const int g_hi = (c < nc) ? c_start[c] / group_keys : n_groups;
+      const int g_lo = (c == 0) ? 0 : c_start[c - 1] / group_keys + 1;
+      for (int gi = g_lo; gi <= g_hi; ++gi) g_first[gi] = c;
+    }
+  }
 }
 
 }  // namespace
@@ -110,7 +125,7 @@ hipError_t launch_plan_chunks(const PrefillDims& d, const int32_t* shot_offsets,
   KernelTimer timer(kKernelPlan, s);
   hipLaunchKernelGGL(plan_chunks_kernel, dim3(d.P), dim3(kPlanThreads), 0, s, shot_offsets, d.share, d.n_shots,
                      d.n_tokens, w.chunk_keys, w.max_c, status, w.n_chunks, w.chunk_start, w.chunk_len,
-                     w.seg_first);
+                     w.seg_first, w.group_keys, w.n_groups, w.group_first);
   return hipGetLastError();
 }
 

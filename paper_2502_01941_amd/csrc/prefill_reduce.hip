@@ -16,13 +16,15 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(const float* __
                                                                  const int32_t* __restrict__ n_chunks,
                                                                  int H_kv, int R, size_t problem_stride,
                                                                  size_t head_stride, size_t group_stride,
-                                                                 int group_chunks,
+                                                                 int n_groups,
                                                                  float* __restrict__ row_stat) {
   const int g = blockIdx.x, p = blockIdx.y;
   const int nl = kStatThreads / R;  // group lanes
   const int tid = threadIdx.x;
   const int r = tid % R, gl = tid / R;
-  const int ng = ceil_div(n_chunks[p], group_chunks);  // groups that hold chunks
+  // entries to combine: every score workgroup's statistic (-inf from one without chunks), or on the
+  // generic path the partial of every chunk
+  const int ng = n_groups > 0 ? (n_chunks[p] > 0 ? n_groups : 0) : n_chunks[p];
   const float* base = group_stat + p * problem_stride + g * head_stride;
   // two passes over the lane's share (second one out of cache): the maximum first, then the sum of
   // 2^(x - max) with independent loads
@@ -107,7 +109,7 @@ hipError_t launch_row_stats(const PrefillDims& d, const PrefillWorkspace& w, hip
   const size_t head_stride = own ? w.n_groups * R : R;
   const size_t group_stride = own ? R : heads * R;
   hipLaunchKernelGGL(row_stats_kernel, dim3(d.H_kv, d.P), dim3(kStatThreads), 0, s, w.group_stat, w.n_chunks,
-                     d.H_kv, d.R, problem_stride, head_stride, group_stride, w.group_chunks, w.row_stat);
+                     d.H_kv, d.R, problem_stride, head_stride, group_stride, own ? w.n_groups : 0, w.row_stat);
   return hipGetLastError();
 }
 

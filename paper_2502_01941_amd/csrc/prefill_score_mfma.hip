@@ -175,8 +175,8 @@ template <int NQB>
 __global__ __launch_bounds__(PairShape<NQB>::kThreads, PairShape<NQB>::kMinWavesPerSimd) void
 score_partials_mfma_kernel(
     const bf16_t* __restrict__ q_obs, const bf16_t* __restrict__ k, int n_tokens, int H, int H_kv, int W,
-    int n_rows, float c, const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ chunk_start,
-    const int32_t* __restrict__ chunk_len, int max_c, int chunks_per_group,
+    int n_rows, float c, const int32_t* __restrict__ group_first, const int32_t* __restrict__ chunk_start,
+    const int32_t* __restrict__ chunk_len, int max_c,
     float* __restrict__ partial, float* __restrict__ group_stat) {
   typedef PairShape<NQB> S;
   constexpr int NQW = S::kNQW;
@@ -186,10 +186,15 @@ score_partials_mfma_kernel(
   const int lane = threadIdx.x % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int g = blockIdx.y, p = blockIdx.z;
-  const int nc = n_chunks[p];
-  const int c_begin = blockIdx.x * chunks_per_group;
-  if (c_begin >= nc) return;  // the whole workgroup leaves together, before any barrier
-  const int c_end = min(c_begin + chunks_per_group, nc);
+  // this workgroup's chunks: those that start inside its slice of the key axis
+  const int32_t* gf = group_first + static_cast<size_t>(p) * (gridDim.x + 1) + blockIdx.x;
+  const int c_begin = gf[0], c_end = gf[1];
+  if (c_begin >= c_end) {  // no chunk starts here (or the problem's offsets are bad): the whole
+                           // workgroup leaves together, before any barrier
+    for (int r = threadIdx.x; r < R; r += S::kThreads)
+      group_stat[((static_cast<size_t>(p) * H_kv + g) * gridDim.x + blockIdx.x) * R + r] = -INFINITY;
+    return;
+  }
 
   const int32_t* cs = chunk_start + static_cast<size_t>(p) * max_c;
   const int32_t* cl = chunk_len + static_cast<size_t>(p) * max_c;
@@ -231,27 +236,48 @@ score_partials_mfma_kernel(
 #pragma unroll
   for (int q = 0; q < NQW; ++q) { m_run[q] = -INFINITY; l_run[q] = 0.f; l_grp[q] = 0.f; }
 
-  // A finished chunk's statistic, log2(sum_k 2^z_k) per query, is stored one block later, ahead of that iteration's loads: the
-  // wait that follows a store also covers it, so it gets a whole block of compute to complete.  Row
-  // r of the partial array is query (lane%32)*NQB + qb; lanes 0..31 store this wave's query blocks.
-  float pend[NQW];  // log2 of the chunk's sum of exponentials per query
-  int pend_c = -1;
+  // A finished chunk's statistic, log2(sum_k 2^z_k) per query, waits in registers until kStash chunks
+  // have finished (or the stream ends) and is then stored right after a barrier, ahead of that
+  // iteration's loads: vector stores share the loads' completion counter, so a store inside the
+  // streaming loop puts its own latency into the wait for the next block, and the fewer of them the
+  // better.  Both lane halves hold a query's value; chunk j of the batch is kept by the lanes of half
+  // j / 4 in slot j % 4.  Row r of the partial array is query (lane%32)*NQB + qb.
+  constexpr int kStash = 8;
+  float stash[4][NQW];
+#pragma unroll
+  for (int sl = 0; sl < 4; ++sl)
+#pragma unroll
+    for (int q = 0; q < NQW; ++q) stash[sl][q] = 0.f;
+  int n_stash = 0, stash_c0 = 0;
+  const int my_half = lane >> 5;
+  auto stash_put = [&](const float (&val)[NQW], int chunk) {
+    if (n_stash == 0) stash_c0 = chunk;
+    const bool mine = (n_stash >> 2) == my_half;
+    const int slot = n_stash & 3;
+#pragma unroll
+    for (int sl = 0; sl < 4; ++sl)
+#pragma unroll
+      for (int q = 0; q < NQW; ++q) stash[sl][q] = (mine && sl == slot) ? val[q] : stash[sl][q];
+    ++n_stash;
+  };
   auto flush = [&]() {
-    float* dst = out + static_cast<size_t>(pend_c) * H_kv * R + (lane & 31) * NQB + qb0;
-    if (lane < 32) {
 #pragma unroll
-      for (int q = 0; q < NQW; ++q)
-        if ((qb0 + q) * 32 + lane >= n_rows) pend[q] = -INFINITY;
-      if (NQW == 4) {
-        *reinterpret_cast<float4*>(dst) = make_float4(pend[0], pend[1 % NQW], pend[2 % NQW], pend[3 % NQW]);
-      } else if (NQW == 2) {
-        *reinterpret_cast<float2*>(dst) = make_float2(pend[0], pend[NQW - 1]);
-      } else {
+    for (int sl = 0; sl < 4; ++sl) {
+      const int j = sl + 4 * my_half;
+      if (j < n_stash) {
+        float* dst = out + static_cast<size_t>(stash_c0 + j) * H_kv * R + (lane & 31) * NQB + qb0;
+        if (NQW == 4) {
+          *reinterpret_cast<float4*>(dst) =
+              make_float4(stash[sl][0], stash[sl][1 % NQW], stash[sl][2 % NQW], stash[sl][3 % NQW]);
+        } else if (NQW == 2) {
+          *reinterpret_cast<float2*>(dst) = make_float2(stash[sl][0], stash[sl][NQW - 1]);
+        } else {
 #pragma unroll
-        for (int q = 0; q < NQW; ++q) dst[q] = pend[q];
+          for (int q = 0; q < NQW; ++q) dst[q] = stash[sl][q];
+        }
       }
     }
-    pend_c = -1;
+    n_stash = 0;
   };
 
   // Stream of 32-key blocks over the workgroup's chunks.  `cur` sits in ring slot cur_buf; up to
@@ -306,7 +332,7 @@ score_partials_mfma_kernel(
     else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * S::kLoads) : "memory");
     // ... and after the barrier so has the partner's; the pair is also done reading the block before
     if (S::kWaves > 1) asm volatile("s_barrier" ::: "memory");
-    if (pend_c >= 0) flush();
+    if (n_stash == kStash) flush();
     if (new_valid) {
 #pragma unroll
       for (int i = 0; i < kLook; ++i)
@@ -330,15 +356,17 @@ score_partials_mfma_kernel(
     first_block = false;
 
     if (cur_rem <= kBlockKeys) {  // last block of its chunk: add up the lane halves (same reference)
+      float val[NQW];
 #pragma unroll
       for (int q = 0; q < NQW; ++q) {
         const float l = l_run[q] + __shfl_xor(l_run[q], 32, kWave);
-        // log2(0) = -inf: a query that saw none of the chunk's keys
-        pend[q] = (l > 0.f) ? m_run[q] + __builtin_amdgcn_logf(l) : -INFINITY;
+        // log2(0) = -inf: a query that saw none of the chunk's keys; so is a padding query row
+        val[q] = (l > 0.f && (qb0 + q) * 32 + (lane & 31) < n_rows) ? m_run[q] + __builtin_amdgcn_logf(l)
+                                                                     : -INFINITY;
         l_grp[q] += l;
         l_run[q] = 0.f;  // the reference carries over to the next chunk
       }
-      pend_c = cur_c;
+      stash_put(val, cur_c);
     }
     if (n_q == 0) break;
     cur_c = q_c[0]; cur_key0 = q_key0[0]; cur_rem = q_rem[0];
@@ -347,7 +375,7 @@ score_partials_mfma_kernel(
     --n_q;
     cur_buf = ring_slot(cur_buf + 1);
   }
-  if (pend_c >= 0) flush();
+  if (n_stash > 0) flush();
   // the same statistic over all of the workgroup's chunks, from which the row denominators are built
   if (lane < 32) {
     float* dst = group_stat + ((static_cast<size_t>(p) * H_kv + g) * gridDim.x + blockIdx.x) * R +
@@ -361,17 +389,18 @@ score_partials_mfma_kernel(
 
 }  // namespace
 
-int score_group_chunks(int P, int H_kv, int max_c) {
-#ifdef SHOTKV_CHUNKS_PER_GROUP
-  return SHOTKV_CHUNKS_PER_GROUP < 2 ? 2 : SHOTKV_CHUNKS_PER_GROUP;  // at least 2: the kernel's own statistics array
+int score_group_keys(int P, int H_kv, int n_tokens) {
+#ifdef SHOTKV_SCORE_GROUP_KEYS
+  return SHOTKV_SCORE_GROUP_KEYS;
 #else
-  // enough workgroups to keep 256 CUs x 6 resident pairs busy several times over, while a pair
-  // amortises its query registers over as many chunks as that allows
-  const long total_chunks = static_cast<long>(max_c) * H_kv * P;
-  long cpg = total_chunks / 16384L;
-  if (cpg < 2) cpg = 2;
-  if (cpg > 8) cpg = 8;
-  return static_cast<int>(cpg);
+  // a workgroup takes the chunks that start inside a slice of the key axis: slices long enough to
+  // amortise its query registers, short enough that 256 CUs x 6 resident pairs are kept busy several
+  // times over (about 16K workgroups for a large batch)
+  const long total_keys = static_cast<long>(n_tokens) * H_kv * P;
+  long keys = (total_keys / 16384L + 255) / 256 * 256;
+  if (keys < 512) keys = 512;
+  if (keys > 2048) keys = 2048;
+  return static_cast<int>(keys);
 #endif
 }
 
@@ -382,14 +411,13 @@ bool score_uses_mfma(const PrefillDims& d) {
 
 hipError_t launch_score_partials_mfma(const PrefillDims& d, const void* q_obs, const void* k,
                                       const PrefillWorkspace& w, hipStream_t s) {
-  const int cpg = w.group_chunks;
   const dim3 grid(w.n_groups, d.H_kv, d.P);
   const float c = d.sm_scale * kLog2e;
   KernelTimer timer(kKernelScore, s);
 #define SHOTKV_LAUNCH_SCORE(NQB)                                                                      \
   hipLaunchKernelGGL(score_partials_mfma_kernel<NQB>, grid, dim3(PairShape<NQB>::kThreads), 0, s,     \
                      static_cast<const bf16_t*>(q_obs), static_cast<const bf16_t*>(k), d.n_tokens, d.H, \
-                     d.H_kv, d.W, d.R_rows, c, w.n_chunks, w.chunk_start, w.chunk_len, w.max_c, cpg, w.partial,      \
+                     d.H_kv, d.W, d.R_rows, c, w.group_first, w.chunk_start, w.chunk_len, w.max_c, w.partial,      \
                      w.group_stat)
   switch (d.R / 32) {
     case 1: SHOTKV_LAUNCH_SCORE(1); break;
