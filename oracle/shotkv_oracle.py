@@ -224,6 +224,34 @@ def prefill_compress(q_obs, k, v, shot_offsets, budget_tokens, sm_scale, mode=SE
     return out
 
 
+def causal_attention(q, k, v, sm_scale):
+    """Textbook causal softmax attention of a whole prompt, grouped-query layout.
+
+    This is the attention pass the prefill phase of a decoder runs anyway; its last W query rows are the
+    observation-window rows whose weights Eq. 3 pools (window_attention gives exactly those weights), so a
+    kernel that computes this pass can emit the scores of Eq. 3 without reading K a second time.
+
+    q: [H, N, D]; k, v: [H_kv, N, D].  Query i of head h sees keys 0..i of KV head h // G, weights are
+    softmax(sm_scale * <q_i, k_t>).  Returns out [H, N, D] float64.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    kk = np.asarray(k, dtype=np.float64)
+    vv = np.asarray(v, dtype=np.float64)
+    H, N, D = q.shape
+    H_kv = kk.shape[0]
+    assert kk.shape == (H_kv, N, D) and vv.shape == (H_kv, N, D) and H % H_kv == 0
+    G = H // H_kv
+    out = np.zeros((H, N, D), dtype=np.float64)
+    for h in range(H):
+        g = h // G
+        z = float(sm_scale) * (q[h] @ kk[g].T)           # [N, N] logits
+        for i in range(N):
+            row = z[i, : i + 1]
+            e = np.exp(row - row.max())
+            out[h, i] = (e / e.sum()) @ vv[g, : i + 1]
+    return out
+
+
 def prefill_compress_per_kv_head(q_obs, k, v, shot_offsets, budget_tokens, sm_scale,
                                  mode=SELECT_PREFIX, scores_override=None):
     """Variant of phase 1 in which every KV head keeps its own set of shots.

@@ -311,3 +311,44 @@ def test_per_kv_head_with_identical_heads_equals_the_layer_selection():
         np.testing.assert_array_equal(h["selected"], layer["selected"])
         np.testing.assert_array_equal(h["kept_positions"], layer["kept_positions"])
         np.testing.assert_allclose(h["scores"] * Hkv, layer["scores"], rtol=1e-12)
+
+
+# ---- causal_attention: the prompt's own attention pass (for the entry point that fuses scoring into it)
+
+def test_causal_attention_hand_example_and_closed_forms():
+    """H=1, D=1, three tokens, sm_scale = ln 2 so that weights are powers of two:
+    q = (1, 1, 2), k = (0, 1, 2), v = (8, 4, 2).  Row 0 sees key 0 only -> 8.  Row 1: weights 2^0 : 2^1 ->
+    (8 + 2*4)/3 = 16/3.  Row 2 (q=2): weights 2^0 : 2^2 : 2^4 -> (8 + 4*4 + 16*2)/21 = 56/21 = 8/3."""
+    q = np.array([[[1.0], [1.0], [2.0]]]); k = np.array([[[0.0], [1.0], [2.0]]]); v = np.array([[[8.0], [4.0], [2.0]]])
+    out = orc.causal_attention(q, k, v, np.log(2.0))
+    np.testing.assert_allclose(out[0, :, 0], [8.0, 16.0 / 3.0, 8.0 / 3.0], rtol=1e-14)
+    # all keys equal: every row is the running mean of V, whatever the queries are
+    rng = np.random.default_rng(5)
+    q = rng.standard_normal((4, 9, 8)); k = np.tile(rng.standard_normal((2, 1, 8)), (1, 9, 1))
+    v = rng.standard_normal((2, 9, 8))
+    out = orc.causal_attention(q, k, v, 0.3)
+    running = np.cumsum(v, axis=1) / np.arange(1, 10)[None, :, None]
+    for h in range(4):
+        np.testing.assert_allclose(out[h], running[h // 2], rtol=1e-12)
+
+
+def test_causal_attention_matches_library_attention_and_the_window_weights():
+    """Third opinion: torch's scaled_dot_product_attention (causal, grouped heads) in float64.  And the last
+    W rows are the window rows of Eq. 3: out[:, N-W:] = window_attention weights @ V."""
+    rng = np.random.default_rng(11)
+    H, H_kv, N, D, W = 6, 2, 37, 16, 5
+    q = rng.standard_normal((H, N, D)); k = rng.standard_normal((H_kv, N, D)); v = rng.standard_normal((H_kv, N, D))
+    scale = 1.0 / np.sqrt(D)
+    out = orc.causal_attention(q, k, v, scale)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[None], torch.from_numpy(k)[None], torch.from_numpy(v)[None], is_causal=True,
+        scale=scale, enable_gqa=True)[0].numpy()
+    np.testing.assert_allclose(out, ref, rtol=1e-10, atol=1e-12)
+    p = orc.window_attention(q[:, N - W:], k, scale)             # [H, W, N]
+    G = H // H_kv
+    for h in range(H):
+        np.testing.assert_allclose(out[h, N - W:], p[h] @ v[h // G], rtol=1e-12, atol=1e-14)
+    # a transposed operand or a dropped mask would show: the first row is v[0], row i ignores keys > i
+    np.testing.assert_allclose(out[:, 0], np.repeat(v[:, 0], G, axis=0), rtol=1e-14)
+    k2 = k.copy(); v2 = v.copy(); k2[:, 20:] += 3.0; v2[:, 20:] -= 1.0
+    np.testing.assert_array_equal(orc.causal_attention(q, k2, v2, scale)[:, :20], out[:, :20])
