@@ -160,6 +160,33 @@ SHOTKV_API int shotkv_select_and_compact(const shotkv_config* cfg, int32_t P, in
                               void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Prefill compression fused into the prompt's own attention pass (Section 5.1, Eq. 3-6; the appendix on
+ * limitations names kernel-level optimisation of the scoring step as open).  The prefill phase of a
+ * decoder computes causal attention for every prompt position anyway, and the last W query rows of that
+ * pass are the observation-window rows whose weights Eq. 3 pools.  This entry point computes
+ *
+ *   attn_out [P][H][n_tokens][D] float   softmax(sm_scale * Q K^T) V, causal, query head h on KV head h / G
+ *
+ * for the whole prompt and takes the window rows' weights from the same pass, so K is not read a second
+ * time for scoring; steps (2)-(4) of shotkv_prefill_compress then run unchanged.
+ *
+ *   q   [P][H][n_tokens][D] dtype   all query rows of the layer (the last W are the window queries)
+ *
+ * Every other argument is as in shotkv_prefill_compress, and so is every result: shot_scores agree with
+ * that entry point's to rounding.  Shapes: bf16, head_dim 128, per-layer head mode; anything else returns
+ * SHOTKV_E_SHAPE.  The workspace (shotkv_prefill_attention_workspace_bytes) also holds a packed copy of V.
+ */
+SHOTKV_API size_t shotkv_prefill_attention_workspace_bytes(const shotkv_config* cfg, int32_t P, int32_t n_tokens,
+                                                int32_t n_shots);
+SHOTKV_API int shotkv_prefill_attention_compress(const shotkv_config* cfg, int32_t P, int32_t n_tokens, int32_t n_shots,
+                                      const void* q, const void* k, const void* v,
+                                      const int32_t* shot_offsets, const int32_t* budget_tokens,
+                                      float* attn_out, void* k_out, void* v_out, int32_t cap,
+                                      int32_t* kept_positions, int32_t* kept_count, float* shot_scores,
+                                      uint8_t* shot_selected, int32_t* status, void* workspace,
+                                      size_t workspace_bytes, void* stream);
+
+/*
  * Decode state of one layer for S sequences: caller-owned device buffers.
  * The prefill cache is what shotkv_prefill_compress produced and is never written here ("compressed
  * once and remains fixed", Section 5.1).  Generated tokens live in a pool of n_slots slots per

@@ -86,6 +86,7 @@ struct PrefillWorkspace {
   float*   row_stat;      // [P][H_kv][R]  log2 of the row's sum of exponentials over all chunks
   float*   chunk_mass;    // [P][maxC]
   float*   scores;        // [P][n_shots]
+  void*    vt;            // fused attention path only: V packed into 32-key blocks [P][H_kv][blocks][D][32]
   int32_t  max_c;
   int32_t  chunk_keys;
   int32_t  group_keys;    // keys per slice of the key axis, 0 on the generic path
@@ -98,7 +99,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int score_group_keys(int P, int H_kv, int n_tokens);  // keys per workgroup of the matrix-core score kernel
 
 inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_tokens, int n_shots,
-                                      bool mfma_score) {
+                                      bool mfma_score, size_t vt_bytes = 0) {
   PrefillWorkspace w{};
   w.chunk_keys = mfma_score ? kChunkKeys : kChunkKeysGeneric;
   w.max_c = max_chunks(n_tokens, n_shots, w.chunk_keys);
@@ -122,6 +123,7 @@ inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_
   w.row_stat = reinterpret_cast<float*>(take(P_ * H_kv * R * 4));
   w.chunk_mass = reinterpret_cast<float*>(take(P_ * C * 4));
   w.scores = reinterpret_cast<float*>(take(P_ * S * 4 + 4));
+  w.vt = vt_bytes ? take(vt_bytes) : nullptr;
   w.bytes = off;
   return w;
 }
@@ -155,6 +157,13 @@ hipError_t launch_compact(const PrefillDims& d, const void* k, const void* v, vo
                           hipStream_t s);
 
 bool score_uses_mfma(const PrefillDims& d);
+
+// causal attention forward that also writes the window rows' softmax partials and row denominators
+bool attention_supported(const PrefillDims& d);
+int attention_key_blocks(int n_tokens);
+hipError_t launch_pack_vt(const PrefillDims& d, const void* v, void* vt, hipStream_t s);
+hipError_t launch_attention_scores(const PrefillDims& d, const void* q, const void* k, const void* vt,
+                                   float* attn_out, const PrefillWorkspace& w, hipStream_t s);
 
 struct DecodeDims {
   int S, H, H_kv, G, D, dtype, cap, n_slots, budget, step, n_splits, split_tokens;

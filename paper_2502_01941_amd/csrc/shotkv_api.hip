@@ -268,6 +268,61 @@ int shotkv_prefill_compress(const shotkv_config* cfg, int32_t P, int32_t n_token
   return from_hip(e);
 }
 
+// dims and workspace of the fused attention entry point: the row stride is exactly G * W (no matrix-core
+// row padding: the attention kernel writes every row that exists), chunks as on the matrix-core path
+static int make_attention_dims(const shotkv_config* cfg, int P, int n_tokens, int n_shots, PrefillDims* d) {
+  const int rc = make_prefill_dims(cfg, P, n_tokens, n_shots, d);
+  if (rc != SHOTKV_OK) return rc;
+  if (cfg->head_mode != SHOTKV_HEADS_PER_LAYER) return SHOTKV_E_SHAPE;
+  if (!attention_supported(*d)) return SHOTKV_E_SHAPE;
+  d->R = d->R_rows;
+  return SHOTKV_OK;
+}
+
+static PrefillWorkspace carve_attention(const PrefillDims& d, void* base) {
+  const size_t vt_bytes = static_cast<size_t>(d.P) * d.H_kv * attention_key_blocks(d.n_tokens) * 32 * d.D * 2;
+  return carve_prefill(base, d.P, d.H_kv, d.R, d.n_tokens, d.n_shots, true, vt_bytes);
+}
+
+size_t shotkv_prefill_attention_workspace_bytes(const shotkv_config* cfg, int32_t P, int32_t n_tokens,
+                                                int32_t n_shots) {
+  PrefillDims d;
+  if (make_attention_dims(cfg, P, n_tokens, n_shots, &d) != SHOTKV_OK) return 0;
+  return carve_attention(d, nullptr).bytes;
+}
+
+int shotkv_prefill_attention_compress(const shotkv_config* cfg, int32_t P, int32_t n_tokens, int32_t n_shots,
+                                      const void* q, const void* k, const void* v,
+                                      const int32_t* shot_offsets, const int32_t* budget_tokens,
+                                      float* attn_out, void* k_out, void* v_out, int32_t cap,
+                                      int32_t* kept_positions, int32_t* kept_count, float* shot_scores,
+                                      uint8_t* shot_selected, int32_t* status, void* workspace,
+                                      size_t workspace_bytes, void* stream) {
+  PrefillDims d;
+  const int rc = make_attention_dims(cfg, P, n_tokens, n_shots, &d);
+  if (rc != SHOTKV_OK) return rc;
+  if (cap < 1) return SHOTKV_E_SHAPE;
+  if (!q || !k || !v || !shot_offsets || !budget_tokens || !attn_out || !k_out || !v_out || !kept_positions ||
+      !kept_count || !status || !workspace)
+    return SHOTKV_E_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(attn_out) || !aligned16(k_out) ||
+      !aligned16(v_out) || !aligned16(workspace))
+    return SHOTKV_E_ALIGN;
+  const PrefillWorkspace w = carve_attention(d, workspace);
+  if (workspace_bytes < w.bytes) return SHOTKV_E_WORKSPACE;
+  float* scores = shot_scores ? shot_scores : w.scores;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_plan_chunks(d, shot_offsets, status, w, s);
+  if (e == hipSuccess) e = launch_pack_vt(d, v, w.vt, s);
+  if (e == hipSuccess) e = launch_attention_scores(d, q, k, w.vt, attn_out, w, s);
+  if (e == hipSuccess) e = launch_chunk_mass(d, w, s);
+  if (e == hipSuccess)
+    e = launch_reduce_select(d, true, true, scores, shot_offsets, budget_tokens, cap, kept_count,
+                             shot_selected, status, kept_positions, w, s);
+  if (e == hipSuccess) e = launch_compact(d, k, v, k_out, v_out, cap, kept_positions, kept_count, s);
+  return from_hip(e);
+}
+
 static int make_decode_dims(const shotkv_config* cfg, int S, int cap, int n_slots, DecodeDims* d) {
   const int rc = check_config(cfg);
   if (rc != SHOTKV_OK) return rc;

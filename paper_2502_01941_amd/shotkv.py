@@ -27,6 +27,7 @@ STATIC_SCRATCH_BYTES = 8 << 20
 EXPORTS = (
     "shotkv_strerror", "shotkv_abi_version", "shotkv_prefill_workspace_bytes",
     "shotkv_prefill_compress", "shotkv_prefill_scores", "shotkv_select_and_compact",
+    "shotkv_prefill_attention_workspace_bytes", "shotkv_prefill_attention_compress",
     "shotkv_decode_workspace_bytes", "shotkv_decode_step", "shotkv_decode_step_static",
     "shotkv_profile_enable",
     "shotkv_profile_read",
@@ -81,6 +82,11 @@ def load_library() -> ctypes.CDLL:
     lib.shotkv_select_and_compact.restype = ctypes.c_int
     lib.shotkv_select_and_compact.argtypes = [cfgp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp,
                                               vp, vp, vp, vp, sz, vp]
+    lib.shotkv_prefill_attention_workspace_bytes.restype = sz
+    lib.shotkv_prefill_attention_workspace_bytes.argtypes = [cfgp, i32, i32, i32]
+    lib.shotkv_prefill_attention_compress.restype = ctypes.c_int
+    lib.shotkv_prefill_attention_compress.argtypes = [cfgp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32,
+                                                      vp, vp, vp, vp, vp, vp, sz, vp]
     lib.shotkv_decode_workspace_bytes.restype = sz
     lib.shotkv_decode_workspace_bytes.argtypes = [cfgp, i32, i32, i32]
     lib.shotkv_decode_step.restype = ctypes.c_int
@@ -204,6 +210,40 @@ def prefill_compress(q_obs, k, v, shot_offsets, budget_tokens, cap, sm_scale,
         _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
     _check(rc, "shotkv_prefill_compress")
     return out
+
+
+def prefill_attention_compress(q, k, v, shot_offsets, budget_tokens, cap, window, sm_scale,
+                               select_mode=SELECT_PREFIX, out: PrefillResult | None = None, workspace=None,
+                               attn_out=None):
+    """shotkv_prefill_attention_compress.  q [P,H,N,D] (all query rows), k/v [P,H_kv,N,D], window = W.
+    Returns (attn_out [P,H,N,D] float32, PrefillResult); nothing is synchronised."""
+    P, H, N, D = q.shape
+    _, H_kv, _, _ = k.shape
+    n = shot_offsets.shape[1] - 1
+    cfg = _config(H, H_kv, D, window, k.dtype, sm_scale, select_mode, HEADS_PER_LAYER)
+    lib = load_library()
+    if out is None:
+        out = _alloc_prefill_outputs(k, P, H_kv, cap, D, n)
+    if attn_out is None:
+        attn_out = torch.empty((P, H, N, D), dtype=torch.float32, device=k.device)
+    if workspace is None:
+        nbytes = lib.shotkv_prefill_attention_workspace_bytes(ctypes.byref(cfg), P, N, n)
+        if nbytes == 0:
+            raise ShotKVError("unsupported shape for the fused attention entry point")
+        workspace = torch.empty(int(nbytes), dtype=torch.uint8, device=k.device)
+    rc = lib.shotkv_prefill_attention_compress(
+        ctypes.byref(cfg), P, N, n, _ptr(q, k.dtype, (P, H, N, D), "q"), _ptr(k, None, (P, H_kv, N, D), "k"),
+        _ptr(v, k.dtype, (P, H_kv, N, D), "v"), _ptr(shot_offsets, torch.int32, (P, n + 1), "shot_offsets"),
+        _ptr(budget_tokens, torch.int32, (P,), "budget_tokens"),
+        _ptr(attn_out, torch.float32, (P, H, N, D), "attn_out"),
+        _ptr(out.k_out, k.dtype, (P, H_kv, cap, D), "k_out"), _ptr(out.v_out, k.dtype, (P, H_kv, cap, D), "v_out"),
+        cap, _ptr(out.kept_positions, torch.int32, (P, cap), "kept_positions"),
+        _ptr(out.kept_count, torch.int32, (P,), "kept_count"),
+        _ptr(out.shot_scores, torch.float32, (P, n), "shot_scores"),
+        _ptr(out.shot_selected, torch.uint8, (P, n), "shot_selected"), _ptr(out.status, torch.int32, (P,), "status"),
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
+    _check(rc, "shotkv_prefill_attention_compress")
+    return attn_out, out
 
 
 def prefill_scores(q_obs, k, shot_offsets, sm_scale, workspace=None, head_mode=HEADS_PER_LAYER):

@@ -153,6 +153,16 @@ def prefill_problem(shape: PrefillShape, problem: int, device="cpu", seed: int =
     return q, k, v, off
 
 
+def prefill_all_queries(shape: PrefillShape, problem: int, q_obs, device="cpu", seed: int = 0):
+    """Query rows of every prompt position [H, N, D] for one problem, for the entry point that computes the
+    prompt's whole attention pass: N(0, 1) rows whose last W are the window queries q_obs of
+    prefill_problem, so that both entry points see the same observation window."""
+    H, D, W, N = shape.n_q_heads, shape.head_dim, shape.window, shape.n_tokens
+    q = _randn((H, N, D), shape.dtype, device, _seed(seed, 6, problem))
+    q[:, N - W:] = q_obs
+    return q
+
+
 def prefill_batch(shape: PrefillShape, device="cpu", seed: int = 0, n_problems: int | None = None):
     """All problems of a shape stacked: q_obs [P, H, W, D], k/v [P, H_kv, N, D], offsets [P, n+1] int32,
     budgets [P] int32 (every problem gets shape.budget_tokens)."""
