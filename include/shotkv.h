@@ -83,22 +83,19 @@ typedef struct {
   float   sm_scale;    /* logits = sm_scale * <q, k>                              */
   int32_t select_mode; /* SHOTKV_SELECT_*                                          */
   int32_t head_mode;   /* SHOTKV_HEADS_*                                           */
+  /* Optional per-kernel timing for benchmarks (not part of the method): NULL, or a host array of
+   * 2 * SHOTKV_KERNEL_KINDS hipEvent_t handles created and owned by the caller.  A call records
+   * events [2 * kind] and [2 * kind + 1] on its stream around each kernel of that kind it enqueues;
+   * the caller synchronises and reads elapsed times.  The library creates no objects and keeps no
+   * state between calls.  Kinds, in order: chunk plan, score, row statistics, chunk mass, shot scores
+   * and selection, compaction, decode partial, decode finish, V packing, fused attention. */
+  void* const* timing_events;
 } shotkv_config;
 
 SHOTKV_API const char* shotkv_strerror(int code);
 SHOTKV_API int32_t shotkv_abi_version(void);
 
-/*
- * Per-kernel timing for benchmarks (not part of the method).  While enabled, every kernel the library
- * enqueues is bracketed by HIP events on the caller's stream.  shotkv_profile_read waits for the
- * recorded launches, adds their durations per kernel kind into total_ms[kind] / launches[kind]
- * (host arrays of n_kinds >= SHOTKV_KERNEL_KINDS entries) and forgets them.  Kinds, in order: chunk
- * plan, score, row statistics, chunk mass, shot scores and selection, compaction, decode partial,
- * decode finish.  Process-wide; the events are the only objects the library ever creates.
- */
-#define SHOTKV_KERNEL_KINDS 8
-SHOTKV_API int shotkv_profile_enable(int enable);
-SHOTKV_API int shotkv_profile_read(double* total_ms, int64_t* launches, int32_t n_kinds);
+#define SHOTKV_KERNEL_KINDS 10
 
 /* Bytes of device workspace shotkv_prefill_compress / _scores / _select_and_compact need for P
  * problems of n_tokens tokens and n_shots shots.  0 if the shape is unsupported. */

@@ -49,20 +49,26 @@ __host__ __device__ __forceinline__ int max_chunks(int n_tokens, int n_shots, in
 
 enum KernelKind {
   kKernelPlan = 0, kKernelScore, kKernelRowStats, kKernelChunkMass, kKernelReduceSelect, kKernelCompact,
-  kKernelDecodePartial, kKernelDecodeFinish, kKernelKinds
+  kKernelDecodePartial, kKernelDecodeFinish, kKernelPackVt, kKernelAttention, kKernelKinds
 };
+static_assert(kKernelKinds == SHOTKV_KERNEL_KINDS, "kernel kinds");
 
-// Brackets one kernel launch with HIP events on its stream while profiling is enabled; free otherwise.
+// Brackets one kernel launch with the caller's HIP events for that kind, if the caller passed any.
 class KernelTimer {
  public:
-  KernelTimer(KernelKind kind, hipStream_t stream);
-  ~KernelTimer();
+  KernelTimer(void* const* events, KernelKind kind, hipStream_t stream)
+      : stop_(events ? static_cast<hipEvent_t>(events[2 * kind + 1]) : nullptr), stream_(stream) {
+    if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[2 * kind]), stream);
+  }
+  ~KernelTimer() {
+    if (stop_) (void)hipEventRecord(stop_, stream_);
+  }
   KernelTimer(const KernelTimer&) = delete;
   KernelTimer& operator=(const KernelTimer&) = delete;
 
  private:
-  hipEvent_t stop_ = nullptr;
-  hipStream_t stream_ = nullptr;
+  hipEvent_t stop_;
+  hipStream_t stream_;
 };
 
 // ---- workspace carving (host) -------------------------------------------------------------------
@@ -138,6 +144,7 @@ struct PrefillDims {
   float sm_scale;
   int select_mode;
   int share;  // consecutive problems that read one row of shot_offsets / budget_tokens
+  void* const* timing;  // the caller's timing events, or null
 };
 
 hipError_t launch_plan_chunks(const PrefillDims& d, const int32_t* shot_offsets, int32_t* status,
@@ -168,6 +175,7 @@ hipError_t launch_attention_scores(const PrefillDims& d, const void* q, const vo
 struct DecodeDims {
   int S, H, H_kv, G, D, dtype, cap, n_slots, budget, step, n_splits, split_tokens;
   float sm_scale;
+  void* const* timing;  // the caller's timing events, or null
 };
 
 struct DecodeWorkspace {

@@ -414,7 +414,7 @@ static hipError_t launch_partial_g(const DecodeDims& d, const shotkv_decode_stat
                                    hipStream_t s) {
   const dim3 grid(d.n_splits, d.H_kv, d.S), block(kDecThreads);
   const float c = d.sm_scale * kLog2e;
-  KernelTimer timer(kKernelDecodePartial, s);
+  KernelTimer timer(d.timing, kKernelDecodePartial, s);
 #define SHOTKV_LAUNCH_DEC(GG)                                                                          \
   hipLaunchKernelGGL((decode_partial_kernel<T, D, GG>), grid, block, 0, s,                             \
                      static_cast<const T*>(st.k_prefill), static_cast<const T*>(st.v_prefill),         \
@@ -451,7 +451,7 @@ hipError_t launch_decode_finish(const DecodeDims& d, const shotkv_decode_state& 
                                 float* token_scores, int32_t* evicted_pos, int32_t* status,
                                 const DecodeWorkspace& w, hipStream_t s) {
   if (d.H > kFinMaxHeads || d.n_splits > kDecodeMaxSplits) return hipErrorInvalidValue;
-  KernelTimer timer(kKernelDecodeFinish, s);
+  KernelTimer timer(d.timing, kKernelDecodeFinish, s);
   hipLaunchKernelGGL(decode_finish_kernel, dim3(1 + ceil_div(d.H, kFinHeadsPerGroup), d.S), dim3(kFinThreads), 0, s, w.part_ml, w.part_o, w.z_dec,
                      st.slot_pos, w.new_slot, d.n_slots, d.H, d.D, d.n_splits, d.budget, d.step, out,
                      token_scores, evicted_pos, status);

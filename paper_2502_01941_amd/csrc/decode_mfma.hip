@@ -291,7 +291,7 @@ hipError_t launch_decode_partial_mfma(const DecodeDims& d, const shotkv_decode_s
                                       hipStream_t s) {
   const dim3 grid(d.n_splits, d.H_kv, d.S), block(kThreads);
   const float c = d.sm_scale * kLog2e;
-  KernelTimer timer(kKernelDecodePartial, s);
+  KernelTimer timer(d.timing, kKernelDecodePartial, s);
 #define SHOTKV_LAUNCH_DEC(GG)                                                                           \
   hipLaunchKernelGGL(decode_partial_mfma_kernel<GG>, grid, block, 0, s,                                 \
                      static_cast<const bf16_t*>(st.k_prefill), static_cast<const bf16_t*>(st.v_prefill), \

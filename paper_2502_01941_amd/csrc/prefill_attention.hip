@@ -334,6 +334,7 @@ int attention_key_blocks(int n_tokens) { return ceil_div(n_tokens, kBlockKeys); 
 
 hipError_t launch_pack_vt(const PrefillDims& d, const void* v, void* vt, hipStream_t s) {
   const int nb = attention_key_blocks(d.n_tokens);
+  KernelTimer timer(d.timing, kKernelPackVt, s);
   hipLaunchKernelGGL(pack_vt_kernel, dim3(nb, d.P * d.H_kv), dim3(256), 0, s, static_cast<const bf16_t*>(v),
                      d.n_tokens, nb, static_cast<bf16_t*>(vt));
   return hipGetLastError();
@@ -343,6 +344,7 @@ hipError_t launch_attention_scores(const PrefillDims& d, const void* q, const vo
                                    float* attn_out, const PrefillWorkspace& w, hipStream_t s) {
   const int nb = attention_key_blocks(d.n_tokens);
   const dim3 grid(ceil_div(d.n_tokens, kTileQ), d.H, d.P);
+  KernelTimer timer(d.timing, kKernelAttention, s);
   hipLaunchKernelGGL(attention_scores_kernel, grid, dim3(kThreadsQ), 0, s, static_cast<const bf16_t*>(q),
                      static_cast<const bf16_t*>(k), static_cast<const bf16_t*>(vt), d.n_tokens, nb, d.H, d.H_kv,
                      d.W, d.sm_scale * kLog2e, attn_out, w.n_chunks, w.chunk_start, w.chunk_len, w.max_c, d.R,

@@ -69,7 +69,7 @@ hipError_t launch_compact(const PrefillDims& d, const void* k, const void* v, vo
                           hipStream_t s) {
   const int row_bytes = d.D * (d.dtype == SHOTKV_BF16 ? 2 : 4);
   const dim3 grid(ceil_div(cap, rows_per_block(row_bytes)), d.H_kv, d.P * 2), block(kCopyThreads);
-  KernelTimer timer(kKernelCompact, s);
+  KernelTimer timer(d.timing, kKernelCompact, s);
 #define SHOTKV_LAUNCH_COMPACT(RB)                                                                      \
   hipLaunchKernelGGL(compact_kernel<RB>, grid, block, 0, s, static_cast<const char*>(k),               \
                      static_cast<const char*>(v), static_cast<char*>(k_out), static_cast<char*>(v_out), \

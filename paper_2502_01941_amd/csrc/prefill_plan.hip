@@ -122,7 +122,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
 
 hipError_t launch_plan_chunks(const PrefillDims& d, const int32_t* shot_offsets, int32_t* status,
                               const PrefillWorkspace& w, hipStream_t s) {
-  KernelTimer timer(kKernelPlan, s);
+  KernelTimer timer(d.timing, kKernelPlan, s);
   hipLaunchKernelGGL(plan_chunks_kernel, dim3(d.P), dim3(kPlanThreads), 0, s, shot_offsets, d.share, d.n_shots,
                      d.n_tokens, w.chunk_keys, w.max_c, status, w.n_chunks, w.chunk_start, w.chunk_len,
                      w.seg_first, w.group_keys, w.n_groups, w.group_first);

@@ -93,14 +93,14 @@ __global__ __launch_bounds__(kMassThreads) void chunk_mass_kernel(const float* _
 }  // namespace
 
 hipError_t launch_chunk_mass(const PrefillDims& d, const PrefillWorkspace& w, hipStream_t s) {
-  KernelTimer timer(kKernelChunkMass, s);
+  KernelTimer timer(d.timing, kKernelChunkMass, s);
   hipLaunchKernelGGL(chunk_mass_kernel, dim3(ceil_div(w.max_c, kMassPerBlock), d.P), dim3(kMassThreads), 0, s,
                      w.partial, w.row_stat, w.n_chunks, d.H_kv, d.R, w.max_c, w.chunk_mass);
   return hipGetLastError();
 }
 
 hipError_t launch_row_stats(const PrefillDims& d, const PrefillWorkspace& w, hipStream_t s) {
-  KernelTimer timer(kKernelRowStats, s);
+  KernelTimer timer(d.timing, kKernelRowStats, s);
   // per-workgroup statistics are [P][H_kv][n_groups][R]; without them (one chunk per score workgroup)
   // the per-chunk partials [P][max_c][H_kv][R] are read in their place
   const bool own = w.group_stat != w.partial;

@@ -60,7 +60,7 @@ hipError_t launch_score_partials_generic(const PrefillDims& d, const void* q_obs
                                          const PrefillWorkspace& w, hipStream_t s) {
   const dim3 grid(w.max_c, d.H_kv, d.P), block(kThreads);
   const float c = d.sm_scale * kLog2e;
-  KernelTimer timer(kKernelScore, s);
+  KernelTimer timer(d.timing, kKernelScore, s);
   if (d.dtype == SHOTKV_BF16) {
     hipLaunchKernelGGL(score_partials_generic_kernel<bf16_t>, grid, block, 0, s,
                        static_cast<const bf16_t*>(q_obs), static_cast<const bf16_t*>(k), d.n_tokens,

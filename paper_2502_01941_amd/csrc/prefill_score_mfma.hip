@@ -413,7 +413,7 @@ hipError_t launch_score_partials_mfma(const PrefillDims& d, const void* q_obs, c
                                       const PrefillWorkspace& w, hipStream_t s) {
   const dim3 grid(w.n_groups, d.H_kv, d.P);
   const float c = d.sm_scale * kLog2e;
-  KernelTimer timer(kKernelScore, s);
+  KernelTimer timer(d.timing, kKernelScore, s);
 #define SHOTKV_LAUNCH_SCORE(NQB)                                                                      \
   hipLaunchKernelGGL(score_partials_mfma_kernel<NQB>, grid, dim3(PairShape<NQB>::kThreads), 0, s,     \
                      static_cast<const bf16_t*>(q_obs), static_cast<const bf16_t*>(k), d.n_tokens, d.H, \

@@ -209,7 +209,7 @@ hipError_t launch_reduce_select(const PrefillDims& d, bool with_mass, bool with_
                                 const int32_t* shot_offsets, const int32_t* budget_tokens, int cap,
                                 int32_t* kept_count, uint8_t* shot_selected, int32_t* status,
                                 int32_t* kept_positions, const PrefillWorkspace& w, hipStream_t s) {
-  KernelTimer timer(kKernelReduceSelect, s);
+  KernelTimer timer(d.timing, kKernelReduceSelect, s);
 #define SHOTKV_LAUNCH_RS(M, S)                                                                          \
   hipLaunchKernelGGL((reduce_select_kernel<M, S>), dim3(d.P), dim3(kSelThreads), 0, s, w.seg_first,     \
                      w.chunk_mass, w.max_c, shot_scores,                                                \

@@ -3,8 +3,6 @@
 #include "common.hpp"
 
 #include <atomic>
-#include <mutex>
-#include <vector>
 
 // Scratch memory of shotkv_decode_step_static: one copy per GPU the library runs on, held until the
 // process ends.  In host code this name is only a handle for hipGetSymbolAddress, never an address.
@@ -29,42 +27,6 @@ int static_scratch(void** out) {
   return SHOTKV_OK;
 }
 }  // namespace
-
-// ---- per-kernel timing ---------------------------------------------------------------------------
-
-namespace {
-struct TimedLaunch { int kind; hipEvent_t start, stop; };
-std::mutex g_prof_mutex;
-bool g_prof_enabled = false;
-std::vector<TimedLaunch> g_prof_launches;
-std::vector<hipEvent_t> g_prof_free_events;
-
-hipEvent_t take_event() {
-  if (!g_prof_free_events.empty()) {
-    hipEvent_t e = g_prof_free_events.back();
-    g_prof_free_events.pop_back();
-    return e;
-  }
-  hipEvent_t e = nullptr;
-  if (hipEventCreate(&e) != hipSuccess) return nullptr;
-  return e;
-}
-}  // namespace
-
-KernelTimer::KernelTimer(KernelKind kind, hipStream_t stream) {
-  std::lock_guard<std::mutex> lock(g_prof_mutex);
-  if (!g_prof_enabled) return;
-  hipEvent_t start = take_event(), stop = take_event();
-  if (!start || !stop) return;
-  (void)hipEventRecord(start, stream);
-  g_prof_launches.push_back({static_cast<int>(kind), start, stop});
-  stop_ = stop;
-  stream_ = stream;
-}
-
-KernelTimer::~KernelTimer() {
-  if (stop_) (void)hipEventRecord(stop_, stream_);
-}
 
 hipError_t launch_score_partials_generic(const PrefillDims& d, const void* q_obs, const void* k,
                                          const PrefillWorkspace& w, hipStream_t s);
@@ -114,6 +76,7 @@ int make_prefill_dims(const shotkv_config* cfg, int P, int n_tokens, int n_shots
     d->R = blocks * 32;
   }
   d->select_mode = cfg->select_mode;
+  d->timing = cfg->timing_events;
   d->share = 1;
   if (cfg->head_mode == SHOTKV_HEADS_PER_KV_HEAD) {
     // A KV head with its G query heads is a problem of its own: [P][H_kv][...] tensors are
@@ -154,34 +117,7 @@ const char* shotkv_strerror(int code) {
   }
 }
 
-int32_t shotkv_abi_version(void) { return 2; }
-
-int shotkv_profile_enable(int enable) {
-  std::lock_guard<std::mutex> lock(g_prof_mutex);
-  g_prof_enabled = enable != 0;
-  return SHOTKV_OK;
-}
-
-int shotkv_profile_read(double* total_ms, int64_t* launches, int32_t n_kinds) {
-  if (!total_ms || !launches) return SHOTKV_E_NULL;
-  if (n_kinds < kKernelKinds) return SHOTKV_E_SHAPE;
-  std::lock_guard<std::mutex> lock(g_prof_mutex);
-  for (int i = 0; i < n_kinds; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
-  int rc = SHOTKV_OK;
-  for (const TimedLaunch& t : g_prof_launches) {
-    float ms = 0.f;
-    if (hipEventSynchronize(t.stop) == hipSuccess && hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) {
-      total_ms[t.kind] += ms;
-      launches[t.kind] += 1;
-    } else {
-      rc = SHOTKV_E_LAUNCH;
-    }
-    g_prof_free_events.push_back(t.start);
-    g_prof_free_events.push_back(t.stop);
-  }
-  g_prof_launches.clear();
-  return rc;
-}
+int32_t shotkv_abi_version(void) { return 3; }
 
 size_t shotkv_prefill_workspace_bytes(const shotkv_config* cfg, int32_t P, int32_t n_tokens,
                                       int32_t n_shots) {
@@ -337,6 +273,7 @@ static int make_decode_dims(const shotkv_config* cfg, int S, int cap, int n_slot
   if (d->S > 65535) return SHOTKV_E_SHAPE;
   d->D = cfg->head_dim; d->dtype = cfg->dtype; d->cap = cap; d->n_slots = n_slots;
   d->sm_scale = cfg->sm_scale;
+  d->timing = cfg->timing_events;
   const int total = cap + n_slots;
   d->n_splits = decode_splits(d->S, d->H_kv, total);  // pairs after the per-KV-head rewrite
   d->split_tokens = ceil_div(total, d->n_splits);

@@ -29,12 +29,10 @@ EXPORTS = (
     "shotkv_prefill_compress", "shotkv_prefill_scores", "shotkv_select_and_compact",
     "shotkv_prefill_attention_workspace_bytes", "shotkv_prefill_attention_compress",
     "shotkv_decode_workspace_bytes", "shotkv_decode_step", "shotkv_decode_step_static",
-    "shotkv_profile_enable",
-    "shotkv_profile_read",
 )
 
 KERNEL_KINDS = ("plan", "score", "row_stats", "chunk_mass", "reduce_select", "compact",
-                "decode_partial", "decode_finish")
+                "decode_partial", "decode_finish", "pack_vt", "attention")
 
 
 class ShotKVError(RuntimeError):
@@ -45,7 +43,7 @@ class _Config(ctypes.Structure):
     _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("window", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("sm_scale", ctypes.c_float), ("select_mode", ctypes.c_int32),
-                ("head_mode", ctypes.c_int32)]
+                ("head_mode", ctypes.c_int32), ("timing_events", ctypes.c_void_p)]
 
 
 class _DecodeState(ctypes.Structure):
@@ -95,10 +93,6 @@ def load_library() -> ctypes.CDLL:
     lib.shotkv_decode_step_static.restype = ctypes.c_int
     lib.shotkv_decode_step_static.argtypes = [cfgp, i32, ctypes.POINTER(_DecodeState), i32, vp, vp, vp, vp, vp,
                                               vp, vp, vp]
-    lib.shotkv_profile_enable.restype = ctypes.c_int
-    lib.shotkv_profile_enable.argtypes = [ctypes.c_int]
-    lib.shotkv_profile_read.restype = ctypes.c_int
-    lib.shotkv_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64), i32]
     _lib = lib
     return lib
 
@@ -134,8 +128,41 @@ def _stream():
     return torch.cuda.current_stream().cuda_stream
 
 
+_timers = None      # the KernelTimers that configs made from now on point at, or None
+
+
 def _config(H, H_kv, D, W, dtype, sm_scale, select_mode, head_mode=HEADS_PER_LAYER):
-    return _Config(H, H_kv, D, W, _dtype_code(dtype), float(sm_scale), int(select_mode), int(head_mode))
+    return _Config(H, H_kv, D, W, _dtype_code(dtype), float(sm_scale), int(select_mode), int(head_mode),
+                   _timers.address if _timers is not None else None)
+
+
+class KernelTimers:
+    """Caller-owned HIP events for shotkv_config.timing_events (benchmarks only): one start/stop pair per
+    kernel kind.  Use as a context manager around calls; read() waits and returns {kind: ms} for the kinds
+    whose kernels ran in the last call."""
+
+    def __init__(self):
+        n = len(KERNEL_KINDS)
+        self.events = [torch.cuda.Event(enable_timing=True) for _ in range(2 * n)]
+        for e in self.events:       # a first record creates the underlying event
+            e.record()
+        torch.cuda.synchronize()
+        self._handles = (ctypes.c_void_p * (2 * n))(*[e.cuda_event for e in self.events])
+        self.address = ctypes.cast(self._handles, ctypes.c_void_p)
+
+    def __enter__(self):
+        global _timers
+        self._before, _timers = _timers, self
+        return self
+
+    def __exit__(self, *exc):
+        global _timers
+        _timers = self._before
+
+    def read(self, kinds):
+        torch.cuda.synchronize()
+        return {k: self.events[2 * KERNEL_KINDS.index(k)].elapsed_time(self.events[2 * KERNEL_KINDS.index(k) + 1])
+                for k in kinds}
 
 
 def _per(head_mode, H_kv):
@@ -333,6 +360,7 @@ def decode_step(state: DecodeState, step_index: int, q_new, k_new, v_new, want_s
     """shotkv_decode_step on `state` (updated in place).  q_new [S,H,D], k_new/v_new [S,H_kv,D].
     Results land in state.out / token_scores / evicted_pos / status; nothing is synchronised."""
     S, H, H_kv, D = state.S, state.H, state.H_kv, state.D
+    state.cfg.timing_events = _timers.address if _timers is not None else None
     rc = load_library().shotkv_decode_step(
         ctypes.byref(state.cfg), S, ctypes.byref(state.c_state), int(step_index),
         _ptr(q_new, state.dtype, (S, H, D), "q_new"), _ptr(k_new, state.dtype, (S, H_kv, D), "k_new"),
@@ -355,17 +383,3 @@ def decode_step_static(state: DecodeState, step_index: int, q_new, k_new, v_new,
         _stream())
     _check(rc, "shotkv_decode_step_static")
     return state.out
-
-
-def profile_enable(enable: bool):
-    """shotkv_profile_enable: bracket every kernel launch with HIP events (benchmarks only)."""
-    _check(load_library().shotkv_profile_enable(1 if enable else 0), "shotkv_profile_enable")
-
-
-def profile_read():
-    """shotkv_profile_read: {kernel kind: (total_ms, launches)} since the last read; waits for them."""
-    n = len(KERNEL_KINDS)
-    ms = (ctypes.c_double * n)()
-    cnt = (ctypes.c_int64 * n)()
-    _check(load_library().shotkv_profile_read(ms, cnt, n), "shotkv_profile_read")
-    return {KERNEL_KINDS[i]: (ms[i], cnt[i]) for i in range(n)}

@@ -32,7 +32,7 @@ def test_header_symbols_are_exported(lib):
 
 def test_host_only_entry_points(lib):
     from paper_2502_01941_amd import shotkv
-    assert lib.shotkv_abi_version() == 2
+    assert lib.shotkv_abi_version() == 3
     assert lib.shotkv_strerror(0) == b"ok"
     assert b"workspace" in lib.shotkv_strerror(-3)
     n = shotkv.prefill_workspace_bytes(32, 8, 128, 32, torch.bfloat16, 4, 32768, 160)
