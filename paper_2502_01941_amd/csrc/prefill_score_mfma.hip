@@ -158,6 +158,66 @@ __device__ __forceinline__ void compute_block(lds_cchar* lds_buf, const bf16x8 (
   }
 }
 
+// The same block when a chunk ends inside it: the exact online-softmax update, then the sixteen weights
+// 2^(z - reference) of every query stay in `e` so that the caller can credit them to the chunks on either
+// side of each boundary.  Nothing is added to l_run here.
+template <int NQW, bool MASKED>
+__device__ __forceinline__ void weights_block(lds_cchar* lds_buf, const bf16x8 (&bq)[NQW][8], int lane, int qb0,
+                                              int key0, int rem, int causal_base, int W, float c,
+                                              float (&m_run)[NQW], float (&l_run)[NQW], float (&l_grp)[NQW],
+                                              floatx16 (&e)[NQW]) {
+  const int row = lane & 31, half = lane >> 5;
+  const int base_even = row * kRowBytes + (row >> 2) * 64 + ((half ^ (row & 3)) << 4);
+  lds_cchar* even = lds_buf + base_even;
+  lds_cchar* odd = lds_buf + (base_even ^ 32);
+#pragma unroll
+  for (int q = 0; q < NQW; ++q)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) e[q][v] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    const bf16x8 a = *reinterpret_cast<lds_bf16x8*>(((ks & 1) ? odd : even) + 64 * (ks >> 1));
+#pragma unroll
+    for (int q = 0; q < NQW; ++q) e[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[q][ks], e[q], 0, 0, 0);
+  }
+#pragma unroll
+  for (int q = 0; q < NQW; ++q) {
+    if (MASKED) {
+      const int last_visible = causal_base + ((qb0 + q) * 32 + row) % W;
+      const int limit = min(rem, last_visible - key0 + 1) - 4 * half;
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (8 * (v >> 2) + (v & 3) >= limit) e[q][v] = -INFINITY;
+    }
+    float bm = fmaxf(e[q][0], e[q][1]);
+#pragma unroll
+    for (int v = 2; v < 16; v += 2) bm = fmaxf(fmaxf(bm, e[q][v]), e[q][v + 1]);
+    bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));
+    const float m_new = fmaxf(m_run[q], bm * c);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run[q] - m_safe);
+    l_run[q] *= alpha;
+    l_grp[q] *= alpha;
+    m_run[q] = m_new;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) e[q][v] = __builtin_amdgcn_exp2f(fmaf(e[q][v], c, -m_safe));
+  }
+}
+
+// sum of the weights of key rows [lo, hi) of a block; lo and hi are per lane, already reduced by 4 * half
+__device__ __forceinline__ float rows_sum(const floatx16& e, int lo, int hi) {
+  float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+  for (int v = 0; v < 16; v += 2) {
+    const int r0 = 8 * (v >> 2) + (v & 3), r1 = 8 * ((v + 1) >> 2) + ((v + 1) & 3);
+    s0 += (r0 >= lo && r0 < hi) ? e[v] : 0.f;
+    s1 += (r1 >= lo && r1 < hi) ? e[v + 1] : 0.f;
+  }
+  return s0 + s1;
+}
+
+constexpr int kEndCache = 128;  // chunk ends of a workgroup kept in LDS
+
 template <int NQB>
 struct PairShape {
 #ifndef SHOTKV_SCORE_MAX_WAVES
@@ -182,6 +242,7 @@ score_partials_mfma_kernel(
   constexpr int NQW = S::kNQW;
   constexpr int R = NQB * 32;
   __shared__ __attribute__((aligned(64))) char lds[kRing][kBufBytes];
+  __shared__ int s_end[kEndCache];
 
   const int lane = threadIdx.x % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -280,52 +341,62 @@ score_partials_mfma_kernel(
     n_stash = 0;
   };
 
-  // Stream of 32-key blocks over the workgroup's chunks.  `cur` sits in ring slot cur_buf; up to
-  // kLook = kRing - 1 requested blocks follow it in the next slots (queue q_*[0..n_q)).  A new block is
-  // requested each iteration, right after the barrier that frees the slot of the block before cur.
-  // The table entry of the chunk after the newest requested one is fetched a chunk ahead.
-  constexpr int kLook = kRing - 1;
-  int tab_c = c_begin + 1;  // next chunk, whose table entry is already on its way
-  int tab_key0 = 0, tab_len = 0;
-  if (tab_c < c_end) { tab_key0 = cs[tab_c]; tab_len = cl[tab_c]; }
-  int new_c = c_begin, new_key0 = cs[c_begin], new_rem = cl[c_begin];  // next block to request
-  bool new_valid = true;
-  auto advance = [&]() {  // step (new_*) to its successor block
-    if (new_rem > kBlockKeys) {
-      new_key0 += kBlockKeys;
-      new_rem -= kBlockKeys;
-    } else {
-      new_c = tab_c;
-      new_valid = new_c < c_end;
-      new_key0 = tab_key0;
-      new_rem = tab_len;
-      tab_c = new_c + 1;
-      if (tab_c < c_end) { tab_key0 = cs[tab_c]; tab_len = cl[tab_c]; }
-    }
+  // The workgroup's chunks tile one contiguous span of the key axis, which is walked in blocks of 32
+  // keys that take no notice of chunk boundaries: a block that contains a boundary credits its weights
+  // to the chunks on either side with masked in-lane sums (sentence-sized units end inside most blocks,
+  // shots of hundreds of tokens inside few), and no block carries padding except the span's last.
+  // `cur` sits in ring slot cur_buf; up to kLook = kRing - 1 requested blocks follow it in the next slots.
+  // A new block is requested each iteration, right after the barrier that frees the slot of the block
+  // before cur.
+  const int k_begin = cs[c_begin];
+  const int k_end = cs[c_end - 1] + cl[c_end - 1];
+  // ends of the first chunks go to LDS: one read per boundary instead of a dependent trip to the table
+  for (int i = threadIdx.x; i < min(c_end - c_begin, kEndCache); i += S::kThreads)
+    s_end[i] = cs[c_begin + i] + cl[c_begin + i];
+  __syncthreads();
+  auto chunk_end = [&](int ci) {
+    const int i = ci - c_begin;
+    const int e = i < kEndCache ? s_end[i] : cs[ci] + cl[ci];
+    return __builtin_amdgcn_readfirstlane(e);
   };
-  auto ring_slot = [](int s) { return s >= kRing ? s - kRing : s; };
-
-  int cur_c = new_c, cur_key0 = new_key0, cur_rem = new_rem;
-  issue_block<S::kLoads>(k_plane, new_key0, new_rem, lds_addr, g0, lane);
-  advance();
-  int q_c[kLook], q_key0[kLook], q_rem[kLook];  // indexed with compile-time indices only
+  constexpr int kLook = kRing - 1;
+  auto ring_slot = [](int sl) { return sl >= kRing ? sl - kRing : sl; };
+  int cur_key0 = k_begin, next_key0 = k_begin + kBlockKeys;  // next block to request
+  issue_block<S::kLoads>(k_plane, k_begin, k_end - k_begin, lds_addr, g0, lane);
   int n_q = 0;
 #pragma unroll
-  for (int i = 0; i < kLook; ++i) { q_c[i] = 0; q_key0[i] = 0; q_rem[i] = 0; }
-#pragma unroll
   for (int i = 0; i < kLook - 1; ++i) {
-    if (new_valid) {
-      q_c[i] = new_c; q_key0[i] = new_key0; q_rem[i] = new_rem;
-      issue_block<S::kLoads>(k_plane, new_key0, new_rem, lds_addr + (i + 1) * kBufBytes, g0, lane);
+    if (next_key0 < k_end) {
+      issue_block<S::kLoads>(k_plane, next_key0, k_end - next_key0, lds_addr + (i + 1) * kBufBytes, g0, lane);
       n_q = i + 1;
-      advance();
+      next_key0 += kBlockKeys;
     }
   }
   int cur_buf = 0;
   bool first_block = true;
+  int cur_c = c_begin, cur_end = chunk_end(c_begin);
+
+  // the current chunk is complete: add up the lane halves (same reference), keep its statistic
+  auto finish_chunk = [&]() {
+    float val[NQW];
+#pragma unroll
+    for (int q = 0; q < NQW; ++q) {
+      const float l = l_run[q] + __shfl_xor(l_run[q], 32, kWave);
+      // log2(0) = -inf: a query that saw none of the chunk's keys; so is a padding query row
+      val[q] = (l > 0.f && (qb0 + q) * 32 + (lane & 31) < n_rows) ? m_run[q] + __builtin_amdgcn_logf(l)
+                                                                   : -INFINITY;
+      l_grp[q] += l;
+      l_run[q] = 0.f;  // the reference carries over to the next chunk
+    }
+    if (n_stash == kStash) flush();  // several chunks can end inside one block
+    stash_put(val, cur_c);
+    ++cur_c;
+    cur_end = cur_c < c_end ? chunk_end(cur_c) : INT32_MAX;
+  };
 
   while (true) {
     // this wave's share of `cur` has landed once only the loads of the queued blocks are outstanding
+    // (stores of statistics issued meanwhile are younger than those loads and only make the wait stricter)
     if (n_q == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     else if (n_q == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(S::kLoads) : "memory");
     else if (n_q == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * S::kLoads) : "memory");
@@ -333,45 +404,46 @@ score_partials_mfma_kernel(
     // ... and after the barrier so has the partner's; the pair is also done reading the block before
     if (S::kWaves > 1) asm volatile("s_barrier" ::: "memory");
     if (n_stash == kStash) flush();
-    if (new_valid) {
-#pragma unroll
-      for (int i = 0; i < kLook; ++i)
-        if (i == n_q) { q_c[i] = new_c; q_key0[i] = new_key0; q_rem[i] = new_rem; }
-      issue_block<S::kLoads>(k_plane, new_key0, new_rem, lds_addr + ring_slot(cur_buf + n_q + 1) * kBufBytes,
-                             g0, lane);
+    if (next_key0 < k_end) {
+      issue_block<S::kLoads>(k_plane, next_key0, k_end - next_key0,
+                             lds_addr + ring_slot(cur_buf + n_q + 1) * kBufBytes, g0, lane);
       ++n_q;
-      advance();
+      next_key0 += kBlockKeys;
     }
-    // keys past the end of the chunk and keys a window query may not see yet are masked; both only
-    // happen in a chunk's last block or in the last W keys, so the common block takes the plain path.
+    // keys past the end of the span and keys a window query may not see yet are masked; both only
+    // happen in the span's last block or in the last W keys, so the common block takes the plain path.
     // The workgroup's first block has no reference yet and takes the exact update straight away.
+    const int cur_rem = min(kBlockKeys, k_end - cur_key0);
     const bool masked = cur_rem < kBlockKeys || cur_key0 + kBlockKeys - 1 > causal_base;
     lds_cchar* blk = lds_base + cur_buf * kBufBytes;
-    if (first_block)
-      compute_block<NQW, true, true>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run, l_grp);
-    else if (masked)
-      compute_block<NQW, true, false>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run, l_grp);
-    else
-      compute_block<NQW, false, false>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run, l_grp);
-    first_block = false;
-
-    if (cur_rem <= kBlockKeys) {  // last block of its chunk: add up the lane halves (same reference)
-      float val[NQW];
+    if (cur_end >= cur_key0 + cur_rem) {  // no chunk ends inside the block
+      if (first_block)
+        compute_block<NQW, true, true>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run, l_grp);
+      else if (masked)
+        compute_block<NQW, true, false>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run, l_grp);
+      else
+        compute_block<NQW, false, false>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run, l_grp);
+    } else {
+      floatx16 e[NQW];
+      if (masked)
+        weights_block<NQW, true>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run, l_grp, e);
+      else
+        weights_block<NQW, false>(blk, bq, lane, qb0, cur_key0, cur_rem, causal_base, W, c, m_run, l_run, l_grp, e);
+      int lo = -4 * my_half;
+      do {
+        const int hi = cur_end - cur_key0 - 4 * my_half;
 #pragma unroll
-      for (int q = 0; q < NQW; ++q) {
-        const float l = l_run[q] + __shfl_xor(l_run[q], 32, kWave);
-        // log2(0) = -inf: a query that saw none of the chunk's keys; so is a padding query row
-        val[q] = (l > 0.f && (qb0 + q) * 32 + (lane & 31) < n_rows) ? m_run[q] + __builtin_amdgcn_logf(l)
-                                                                     : -INFINITY;
-        l_grp[q] += l;
-        l_run[q] = 0.f;  // the reference carries over to the next chunk
-      }
-      stash_put(val, cur_c);
+        for (int q = 0; q < NQW; ++q) l_run[q] += rows_sum(e[q], lo, hi);
+        finish_chunk();
+        lo = hi;
+      } while (cur_end < cur_key0 + cur_rem);
+#pragma unroll
+      for (int q = 0; q < NQW; ++q) l_run[q] += rows_sum(e[q], lo, kBlockKeys);
     }
+    first_block = false;
+    if (cur_end == cur_key0 + cur_rem) finish_chunk();  // the chunk ends with the block
     if (n_q == 0) break;
-    cur_c = q_c[0]; cur_key0 = q_key0[0]; cur_rem = q_rem[0];
-#pragma unroll
-    for (int i = 0; i + 1 < kLook; ++i) { q_c[i] = q_c[i + 1]; q_key0[i] = q_key0[i + 1]; q_rem[i] = q_rem[i + 1]; }
+    cur_key0 += kBlockKeys;
     --n_q;
     cur_buf = ring_slot(cur_buf + 1);
   }
