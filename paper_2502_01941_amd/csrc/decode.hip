@@ -299,20 +299,38 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
   // (requested before the slot index above is looked at, so that the two loads travel together)
   // global softmax statistics per head: one wave per head, lanes over the splits; each split's weight
   // 2^(m - M) is kept so that the merge below is a plain weighted sum
-  for (int h = h_lo + wave; h < h_hi; h += kFinWaves) {
+  // (a wave's heads are taken two at a time so that their first loads travel together)
+  for (int h = h_lo + wave; h < h_hi; h += 2 * kFinWaves) {
+    const int h2 = h + kFinWaves;
+    const bool two = h2 < h_hi;
     const float2* ml = part_ml + (head0 + h) * n_splits;
-    float M = -INFINITY;
-    for (int i = lane; i < n_splits; i += kWave) M = fmaxf(M, ml[i].x);
+    const float2* ml2 = part_ml + (head0 + (two ? h2 : h)) * n_splits;
+    float M = -INFINITY, M2 = -INFINITY;
+    for (int i = lane; i < n_splits; i += kWave) {
+      const float a = ml[i].x, b = ml2[i].x;
+      M = fmaxf(M, a);
+      M2 = fmaxf(M2, b);
+    }
     M = wave_max(M);
-    float L = 0.f;
+    M2 = wave_max(M2);
+    float L = 0.f, L2 = 0.f;
     for (int i = lane; i < n_splits; i += kWave) {  // second look at the same few bytes: out of cache
-      const float2 x = ml[i];
+      const float2 x = ml[i], y = ml2[i];
       const float wgt = x.y > 0.f ? __builtin_amdgcn_exp2f(x.x - M) : 0.f;
+      const float wgt2 = y.y > 0.f ? __builtin_amdgcn_exp2f(y.x - M2) : 0.f;
       L += x.y * wgt;
-      if (!retain) s_w[h - h_lo][i] = wgt;
+      L2 += y.y * wgt2;
+      if (!retain) {
+        s_w[h - h_lo][i] = wgt;
+        if (two) s_w[h2 - h_lo][i] = wgt2;
+      }
     }
     L = wave_sum(L);
-    if (lane == 0) { s_M[h] = M; s_invL[h] = 1.f / L; }
+    L2 = wave_sum(L2);
+    if (lane == 0) {
+      s_M[h] = M; s_invL[h] = 1.f / L;
+      if (two) { s_M[h2] = M2; s_invL[h2] = 1.f / L2; }
+    }
   }
   if (new_slot < 0) {  // pool full: the step is void for this sequence
     if (retain) {
@@ -344,7 +362,26 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
   // retention scores and the eviction candidate
   float best_score = INFINITY;
   int best_pos = -1, best_slot = -1, count = 0;
-  for (int slot = tid; slot < n_slots; slot += kFinThreads) {
+  // A pool of budget + 1 slots is one more than a round of threads: the few slots past the last full
+  // round are scored by one wave each, lanes over the heads, and their logits are requested here, ahead
+  // of the main loop, so that they do not cost a dependent trip to memory of their own.
+  constexpr int kMaxExtra = 4;  // per wave
+  int n_extra = n_slots > kFinThreads ? n_slots % kFinThreads : 0;
+  if (n_extra > kMaxExtra * kFinWaves) n_extra = 0;
+  const int n_main = n_slots - n_extra;
+  float ez[kMaxExtra];
+  int epos[kMaxExtra];
+#pragma unroll
+  for (int k = 0; k < kMaxExtra; ++k) {
+    const int slot = n_main + wave + k * kFinWaves;
+    ez[k] = -INFINITY;
+    epos[k] = -1;
+    if (slot < n_slots) {
+      epos[k] = (slot == new_slot) ? step_index : sp[slot];
+      if (lane < H) ez[k] = z_dec[(head0 + lane) * n_slots + slot];
+    }
+  }
+  for (int slot = tid; slot < n_main; slot += kFinThreads) {
     const int pos = (slot == new_slot) ? step_index : sp[slot];
     float score = 0.f;
     if (pos >= 0) {
@@ -357,6 +394,27 @@ __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(
       }
     }
     if (token_scores) token_scores[static_cast<size_t>(s) * n_slots + slot] = score;
+  }
+#pragma unroll
+  for (int k = 0; k < kMaxExtra; ++k) {
+    const int slot = n_main + wave + k * kFinWaves;
+    if (slot < n_slots) {  // wave-uniform
+      const int pos = epos[k];
+      float part = 0.f;
+      if (pos >= 0 && lane < H) part = __builtin_amdgcn_exp2f(ez[k] - s_M[lane]) * s_invL[lane];
+      // same order of the head sum as in the main loop would need a serial add; a tree sum over the
+      // heads differs from it only in rounding, within the score tolerance
+      const float score = wave_sum(part);
+      if (lane == 0) {
+        if (pos >= 0) {
+          ++count;
+          if (slot != new_slot && (best_slot < 0 || evict_before(score, pos, best_score, best_pos))) {
+            best_score = score; best_pos = pos; best_slot = slot;
+          }
+        }
+        if (token_scores) token_scores[static_cast<size_t>(s) * n_slots + slot] = score;
+      }
+    }
   }
   for (int o = kWave / 2; o > 0; o >>= 1) {
     const float os = __shfl_xor(best_score, o, kWave);
