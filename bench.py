@@ -30,7 +30,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `rocprofv3 --pmc` runs of this file, see profiles/score_partials_mfma_model32k_counters.md).  Valid only
 # for the kernel source it was measured on: reported as null once that file's hash differs.
 SCORE_KERNEL_SOURCE = os.path.join(ROOT, "paper_2502_01941_amd", "csrc", "prefill_score_mfma.hip")
-MEASURED_TRAFFIC = {"model32k": {"sha256": "8f222e3d70bc76496aac6e33a7c2a1a008629c854a2992343b887303a3c044b0",
+MEASURED_TRAFFIC = {"model32k": {"sha256": "b5d4b6c6c4bfc1ca72cec8443a4c8c465481b03cb0699bf37087d99811144c03",
                                  "bytes": 9.03e9}}
 
 PREFILL_KINDS = ("plan", "score", "row_stats", "chunk_mass", "reduce_select", "compact")

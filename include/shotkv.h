@@ -42,8 +42,8 @@ extern "C" {
 
 enum { SHOTKV_BF16 = 0, SHOTKV_F32 = 1 };
 
-/* How the ranked walk treats a shot that does not fit (Section 5.1: shots are "selected in descending
- * order until they reach the compression budget").  PREFIX stops at the first misfit (the literal
+/* How the ranked walk treats a shot that does not fit (Section 5.1, the paragraph after Eq. 3: shots
+ * are taken in descending score order up to the budget).  PREFIX stops at the first misfit (the literal
  * reading, default); FIRST_FIT skips it and continues with lower-ranked shots. */
 enum { SHOTKV_SELECT_PREFIX = 0, SHOTKV_SELECT_FIRST_FIT = 1 };
 
@@ -185,13 +185,15 @@ SHOTKV_API int shotkv_prefill_attention_compress(const shotkv_config* cfg, int32
 
 /*
  * Decode state of one layer for S sequences: caller-owned device buffers.
- * The prefill cache is what shotkv_prefill_compress produced and is never written here ("compressed
- * once and remains fixed", Section 5.1).  Generated tokens live in a pool of n_slots slots per
+ * The prefill cache is what shotkv_prefill_compress produced and is never written here (Section 5.1,
+ * Eq. 2: the prefill part is compressed one time only and kept as it is while decoding).  Generated
+ * tokens live in a pool of n_slots slots per
  * sequence; slot_pos holds the generated-token index in each slot, -1 when free (initialise to -1).
  * n_slots must be >= decode_budget + 1 unless the caller guarantees fewer steps than n_slots.
  * Rows of the prefill cache past prefill_count may hold anything: they may be fetched but never
- * influence a result.  decode_budget may change from step to step, e.g. ceil(r_d * (step_index + 1))
- * for the ratio form of Eq. 8.
+ * influence a result.  decode_budget may stay or grow from step to step, e.g. ceil(r_d * (step_index +
+ * 1)) for the ratio form of Eq. 8; a step evicts at most one token, so a budget that shrinks is not
+ * honoured (the cache keeps the size it has).
  * In per-KV-head mode prefill_count is [S][H_kv] and slot_pos [S][H_kv][n_slots]: every KV head has
  * its own live row count and its own slot map.
  */

@@ -138,7 +138,7 @@ inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_
 
 struct PrefillDims {
   int P, n_tokens, n_shots, H, H_kv, G, D, W;
-  int R;       // row stride of the per-row workspace arrays: G * W, padded to 32/64/128/256 on the matrix-core path
+  int R;       // row stride of the per-row workspace arrays: G * W, padded to 32/64/128/192/256 on the matrix-core score path
   int R_rows;  // G * W query rows per KV head that really exist
   int dtype;
   float sm_scale;

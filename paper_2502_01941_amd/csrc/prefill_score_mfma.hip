@@ -1,18 +1,21 @@
 // Window-attention softmax partials on the gfx950 matrix cores (Section 5.1, Eq. 3: alpha_{t,h}).
 //
-// Shape: bf16, head_dim 128, R = G*W in {32, 64, 128} query rows per KV head.
+// Shape: bf16, head_dim 128, up to 256 query rows (G*W) per KV head, instantiated for 1, 2, 4, 6 or 8
+// blocks of 32 rows; rows past G*W are zero operands whose statistics are written as -inf.
 //
-// A workgroup is a pair of waves that walks a range of chunks of one KV head in blocks of 32 keys.
-// Each wave keeps half of the R x 128 window queries in registers as MFMA B operands and computes
-// S^T[32 keys x R/2 queries] = K_blk * Q^T with v_mfma_f32_32x32x16_bf16.  Keys run along the
+// A workgroup is a pair of waves (one wave for a single row block) that takes the chunks starting inside
+// one slice of a KV head's key axis and walks that contiguous span in blocks of 32 keys.  Each wave keeps
+// its share of the window queries in registers as MFMA B operands and computes
+// S^T[32 keys x 32 queries] = K_blk * Q^T per row block with v_mfma_f32_32x32x16_bf16.  Keys run along the
 // accumulator registers and queries along the lanes, so the row-softmax statistics (max and sum over
-// keys) are in-lane reductions; only the two lane halves are merged, once per chunk.
+// keys) are in-lane reductions; only the two lane halves are merged, once per chunk.  A block that
+// contains a chunk boundary credits its weights to the chunks on either side with masked in-lane sums.
 //
 // K blocks are streamed global -> LDS with 16-byte direct-to-LDS loads (whole 256-byte rows, fully
 // coalesced; each wave fetches half of every block) into a ring of three buffers, so two blocks are
 // in flight while one is being consumed; both waves read the whole block back in MFMA A-operand
 // layout.  One s_barrier per block tells the pair that a block has landed and that the buffer of the
-// block before it may be refilled.  With ~150 registers per wave three waves fit on a SIMD.
+// block before it may be refilled.  With ~166 registers per wave three waves fit on a SIMD.
 //
 // LDS layout of a block: key row r starts at r*256 + (r/4)*64 and its 16-byte column c sits in slot
 // c ^ (r%4).  The 64-byte pad per four rows plus the two-bit XOR spread the 16 lanes of a 128-bit LDS
@@ -53,8 +56,8 @@ static_assert(kRing >= 2 && kRing <= 5, "ring depth");
 
 // Issue this wave's share of the direct-to-LDS loads of one 32-key block: groups [g0, g0 + NG).
 // Group i fills rows 4i..4i+3: lane l writes LDS slot l of the group, which is row 4i + l/16, slot
-// l%16, and therefore fetches column (l%16) ^ (l/16) of that row.  Rows past the end of the chunk
-// re-read its last key (they are masked later), so every address stays inside the chunk.
+// l%16, and therefore fetches column (l%16) ^ (l/16) of that row.  Rows past the end of the span
+// (rem keys are left in it) re-read its last key (they are masked later), so every address stays inside it.
 template <int NG>
 __device__ __forceinline__ void issue_block(const char* __restrict__ k_plane, int key0, int rem,
                                             uint32_t lds_addr, int g0, int lane) {
@@ -267,7 +270,7 @@ score_partials_mfma_kernel(
   const int qb0 = wave * NQW;
 
   // B operands: query row (qb0+q)*32 + lane%32, head-dim slice 16*ks + 8*(lane/32) .. +8
-  // Query rows past n_rows = G*W (a row count that is not one of 32/64/128/256) are zero operands; their
+  // Query rows past n_rows = G*W (a row count that is not one of 32/64/128/192/256) are zero operands; their
   // statistics are written as -inf, so they carry no weight further down.
   bf16x8 bq[NQW][8];
 #pragma unroll

@@ -79,7 +79,7 @@ def _ragged_problem(P, H, Hkv, D, W, N, dtype, seed, n_shots, prefix, tail_min):
     (4, 4, 128, 8, 300, torch.float32, 3),        # fp32, D=128
     (8, 2, 64, 24, 500, torch.bfloat16, 5),       # bf16, D=64, W not a power of two
     (8, 4, 128, 64, 800, torch.bfloat16, 5),      # the widest window, G=2 -> 128 rows (matrix-core path)
-    (8, 2, 128, 64, 600, torch.bfloat16, 4),      # the widest window, G=4 -> 256 rows (generic path)
+    (8, 2, 128, 64, 600, torch.bfloat16, 4),      # the widest window, G=4 -> 256 rows (eight row blocks on the matrix-core path)
     (64, 8, 128, 32, 450, torch.bfloat16, 3),     # the most query heads, G=8 -> 256 rows
     (4, 4, 128, 1, 200, torch.bfloat16, 3),       # a single window query
     (28, 4, 128, 32, 1100, torch.bfloat16, 6),    # G=7 -> 224 rows, padded to 256 on the matrix-core path
