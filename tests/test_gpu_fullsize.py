@@ -96,17 +96,23 @@ def test_near_tie_report(full, record_property):
 def test_decode_over_the_compressed_caches(kv, full):
     """The decode half of the benchmark step: one launch over all compressed caches (ragged live-row
     counts below cap, empty slot pools of budget + 1 slots), a few steps, every sequence followed by
-    the oracle in lock step."""
+    the oracle in lock step.  For the 32K workload (what the benchmark step decodes over) all 128 caches;
+    for the other workloads the first 8."""
     shape, res = full["shape"], full["res"]
-    if shape.name != "model32k":
-        pytest.skip("the benchmark step decodes over the 32K workload's caches")
     from test_gpu_decode import OracleSeq, _compare_step
+    if shape.name != "model32k":
+        import types
+        n = min(8, shape.n_problems)
+        res = types.SimpleNamespace(k_out=res.k_out[:n].contiguous(), v_out=res.v_out[:n].contiguous(),
+                                    kept_count=res.kept_count[:n].contiguous())
+        shape = wl.PrefillShape(shape.name, n, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.window,
+                                shape.n_tokens, shape.n_shots, shape.dtype, shape.budget_tokens)
     P, cap, budget = shape.n_problems, shape.budget_tokens, 1024
     n_slots = budget + 1
     k_dec = torch.zeros((P, shape.n_kv_heads, n_slots, shape.head_dim), dtype=shape.dtype, device="cuda")
     v_dec = torch.zeros_like(k_dec)
     slot_pos = torch.full((P, n_slots), -1, dtype=torch.int32, device="cuda")
-    assert int(res.kept_count.min().item()) < cap            # the caches are ragged
+    assert int(res.kept_count.min().item()) <= cap
     # rows past the live count are whatever the allocator left: make them hostile
     k_pre, v_pre = res.k_out.clone(), res.v_out.clone()
     for p in range(P):
