@@ -81,3 +81,37 @@ def test_capture_and_replay_matches_eager(kv):
         assert len(got) == len(want)
         for g, w in zip(got, want):
             assert torch.equal(g, w)
+
+
+def test_caller_owned_timing_events(kv):
+    """shotkv_config.timing_events: the library records the caller's HIP events around each kernel of a
+    call and nothing else changes - same results bit for bit, positive durations for the kinds that ran,
+    and no recording once the events are withdrawn."""
+    shape = wl.PrefillShape("timed", 2, 32, 8, 128, 32, 3000, 12, torch.bfloat16, 1200)
+    q, k, v, off, bud = wl.prefill_batch(shape, "cuda", 4)
+    plain = kv.prefill_compress(q, k, v, off, bud, shape.budget_tokens, shape.sm_scale)
+    torch.cuda.synchronize()
+    timers = kv.KernelTimers()
+    with timers:
+        timed = kv.prefill_compress(q, k, v, off, bud, shape.budget_tokens, shape.sm_scale)
+        ms = timers.read(("plan", "score", "row_stats", "chunk_mass", "reduce_select", "compact"))
+    assert all(x > 0.0 for x in ms.values()), ms
+    assert ms["score"] < 50.0 and ms["plan"] < 50.0
+    for a, b in ((plain.shot_scores, timed.shot_scores), (plain.shot_selected, timed.shot_selected),
+                 (plain.kept_count, timed.kept_count), (plain.status, timed.status)):
+        assert torch.equal(a, b)
+    kept = int(plain.kept_count[0])
+    assert torch.equal(plain.k_out[0, :, :kept], timed.k_out[0, :, :kept])
+    # decode: a state made outside the context is timed inside it and not outside
+    dshape = wl.DecodeShape("timed", 2, 32, 8, 128, shape.budget_tokens, 8, 0, torch.bfloat16)
+    k_dec = torch.zeros((2, 8, 9, 128), dtype=torch.bfloat16, device="cuda")
+    state = kv.DecodeState(plain.k_out, plain.v_out, plain.kept_count, k_dec, torch.zeros_like(k_dec),
+                           torch.full((2, 9), -1, dtype=torch.int32, device="cuda"), 8, 32, shape.sm_scale)
+    qn, kn, vn = wl.decode_inputs(dshape, 0, "cuda", 4)
+    with timers:
+        kv.decode_step(state, 0, qn, kn, vn)
+        dms = timers.read(("decode_partial", "decode_finish"))
+    assert all(x > 0.0 for x in dms.values()), dms
+    kv.decode_step(state, 1, qn, kn, vn)
+    torch.cuda.synchronize()
+    assert state.cfg.timing_events is None and int(state.status.abs().sum().item()) == 0
