@@ -23,7 +23,8 @@
 // K and packed-V blocks are streamed global -> LDS with direct-to-LDS loads into a ring of three stages
 // shared by the four waves (one barrier per block); the LDS layouts are bank-conflict free for the
 // 128-bit operand reads (K as in the score kernel; V^T rows of 64 bytes with a two-bit XOR of the
-// 16-byte column).
+// 16-byte column).  The grid puts the query tile in its slowest dimension, longest tiles first, so that
+// every head's long tiles are dispatched before anybody's short ones.
 #include "common.hpp"
 
 namespace shotkv {
@@ -105,12 +106,13 @@ __device__ __forceinline__ void issue_k(const char* __restrict__ k_plane, int ke
   }
 }
 // V^T slabs [i0, i0 + 2) of a packed block: slab i fills rows (d) 16i..16i+15 of 64 bytes; lane l writes
-// row 16i + l/4, slot l%4 and fetches column (l%4) ^ ((row/2)%4) of that row.
+// row 16i + l/4, slot l%4 and fetches column (l%4) ^ ((row/4)%4) of that row: sixteen consecutive rows,
+// read 16 bytes each by sixteen lanes, then cover the 64 LDS banks exactly once.
 __device__ __forceinline__ void issue_vt(const char* __restrict__ vt_block, uint32_t lds_addr, int i0, int lane) {
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int d = 16 * (i0 + i) + (lane >> 2);
-    const int c = (lane & 3) ^ ((d >> 1) & 3);
+    const int c = (lane & 3) ^ ((d >> 2) & 3);
     const uint32_t off = static_cast<uint32_t>(d * 64 + c * 16);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
@@ -135,8 +137,8 @@ __global__ __launch_bounds__(kThreadsQ, 2) void attention_scores_kernel(
   __shared__ __attribute__((aligned(64))) char lds[kRing][kStageBytes];
   const int lane = threadIdx.x % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const int tile = gridDim.x - 1 - blockIdx.x;  // long tiles first
-  const int h = blockIdx.y, p = blockIdx.z;
+  const int tile = gridDim.z - 1 - blockIdx.z;  // long tiles first, for all heads and problems
+  const int h = blockIdx.x, p = blockIdx.y;
   const int G = H / H_kv, g = h / G;
   const int q0 = tile * kTileQ;
   const int half = lane >> 5;
@@ -294,7 +296,7 @@ __global__ __launch_bounds__(kThreadsQ, 2) void attention_scores_kernel(
         const int d = 32 * t + (lane & 31);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-          const int col = (2 * s + half) ^ ((d >> 1) & 3);
+          const int col = (2 * s + half) ^ ((d >> 2) & 3);
           const bf16x8 a = *reinterpret_cast<lds_bf16x8*>(vblk + d * 64 + col * 16);
           ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_hi[s], ot[t], 0, 0, 0);
           ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_lo[s], ot[t], 0, 0, 0);
@@ -343,7 +345,7 @@ hipError_t launch_pack_vt(const PrefillDims& d, const void* v, void* vt, hipStre
 hipError_t launch_attention_scores(const PrefillDims& d, const void* q, const void* k, const void* vt,
                                    float* attn_out, const PrefillWorkspace& w, hipStream_t s) {
   const int nb = attention_key_blocks(d.n_tokens);
-  const dim3 grid(ceil_div(d.n_tokens, kTileQ), d.H, d.P);
+  const dim3 grid(d.H, d.P, ceil_div(d.n_tokens, kTileQ));
   KernelTimer timer(d.timing, kKernelAttention, s);
   hipLaunchKernelGGL(attention_scores_kernel, grid, dim3(kThreadsQ), 0, s, static_cast<const bf16_t*>(q),
                      static_cast<const bf16_t*>(k), static_cast<const bf16_t*>(vt), d.n_tokens, nb, d.H, d.H_kv,
