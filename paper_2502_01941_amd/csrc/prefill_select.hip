@@ -3,7 +3,11 @@
 // shots in descending order while the budget holds).  One workgroup per problem does all of it:
 //
 //   scores    Score(s_i) = (sum of the masses of the shot's chunks) / k_i;
-//   ranking   bitonic sort in LDS on the key (score descending, shot index ascending);
+//   ranking   bitonic sort on one 64-bit key per shot (score descending, shot index ascending): keys
+//             live in registers, partners less than 64 apart are exchanged with lane shuffles, and
+//             for the larger strides the keys pass through LDS into a transposed layout in which
+//             those strides are lane distances too - two LDS round trips per merge level instead of
+//             one per compare-exchange step;
 //   budget    prefix sum of shot lengths in rank order (or the sequential first-fit walk);
 //   plan      prefix sum of kept lengths in position order gives every retained row's output slot;
 //             the original position of each output row is written in ascending order.
@@ -51,8 +55,80 @@ __device__ int block_exclusive_scan(int* a, int n, int* tmp) {
   return total;
 }
 
-__device__ __forceinline__ bool ranks_before(float sa, int ia, float sb, int ib) {
-  return (sa > sb) || (sa == sb && ia < ib);
+constexpr int kMaxPad = SHOTKV_MAX_SHOTS;            // keys sorted at most (a power of two)
+constexpr int kKeySlots = kMaxPad + kMaxPad / 64;    // one pad slot per 64 keys: transposed reads hit all banks
+static_assert((kMaxPad & (kMaxPad - 1)) == 0 && kMaxPad <= 4 * kSelThreads, "up to four keys per thread");
+
+// One key per shot whose descending order is the ranking: score descending, then index ascending.
+// The float's bits are mapped to an unsigned integer with the same order (-0 ranks with +0); entry i
+// of the padding (i >= n_shots) gets the smallest score word and therefore ranks after every shot.
+__device__ __forceinline__ uint64_t rank_key(float score, int idx) {
+  uint32_t b = __float_as_uint(score);
+  if ((b << 1) == 0u) b = 0u;
+  const uint32_t u = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+  return (static_cast<uint64_t>(u) << 32) | (0xFFFFFFFFu - static_cast<uint32_t>(idx));
+}
+__device__ __forceinline__ uint64_t padding_key(int idx) { return 0xFFFFFFFFu - static_cast<uint32_t>(idx); }
+
+__device__ __forceinline__ uint64_t shuffle_xor64(uint64_t v, int lane_mask) {
+  const uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), lane_mask, kWave);
+  const uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), lane_mask, kWave);
+  return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+// Sorts n_pad keys (a power of two, 64 <= n_pad <= E * 1024) into descending order.  Thread tid holds
+// array elements tid + 1024 * j in k[j]; on return k[j] is the key of rank tid + 1024 * j.  All 1024
+// threads must call it (barriers); threads whose elements lie past n_pad carry dummies.
+// Layouts: "natural" - element t = tid + 1024 j is array index t; "transposed" - it is array index
+// ((t mod 2^hb) << 6) | (t >> hb) with hb = log2(n_pad) - 6, which puts index bits 6.. on the low lane
+// bits.  keys[] holds kKeySlots entries; array index a lives in slot a + a/64.  With n_pad <= 2048 two
+// alternating buffers make one barrier per layout change enough; 4096 keys need a second one.
+template <int E>
+__device__ void sort_keys_descending(uint64_t (&k)[E], int n_pad, uint64_t* keys) {
+  const int tid = threadIdx.x;
+  const int hb = (31 - __clz(n_pad)) - 6;
+  const int low_mask = (1 << hb) - 1;
+  const int second = n_pad <= kMaxPad / 2 ? kKeySlots / 2 : 0;
+  int buf = 0;
+  auto natural = [&](int j) { return tid + kSelThreads * j; };
+  auto transposed = [&](int j) {
+    const int t = tid + kSelThreads * j;
+    return ((t & low_mask) << 6) | (t >> hb);
+  };
+  auto slot = [](int a) { return a + (a >> 6); };
+  auto stage = [&](int size, int stride, int lane_mask, bool in_transposed) {
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const int a = in_transposed ? transposed(j) : natural(j);
+      const uint64_t other = shuffle_xor64(k[j], lane_mask);
+      const bool want_max = ((a & size) == 0) == ((a & stride) == 0);
+      const bool take = want_max ? other > k[j] : other < k[j];
+      k[j] = take ? other : k[j];
+    }
+  };
+  auto relayout = [&](bool to_transposed) {
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const int t = natural(j);
+      if (t < n_pad) keys[buf + slot(to_transposed ? t : transposed(j))] = k[j];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const int t = natural(j);
+      if (t < n_pad) k[j] = keys[buf + slot(to_transposed ? transposed(j) : t)];
+    }
+    if (second) buf ^= second;
+    else __syncthreads();
+  };
+  for (int size = 2; size <= n_pad; size <<= 1) {
+    if (size > kWave) {
+      relayout(true);
+      for (int stride = size >> 1; stride >= kWave; stride >>= 1) stage(size, stride, stride >> 6, true);
+      relayout(false);
+    }
+    for (int stride = min(size >> 1, kWave / 2); stride > 0; stride >>= 1) stage(size, stride, stride, false);
+  }
 }
 
 template <bool MASS, bool SELECT>
@@ -64,17 +140,17 @@ __global__ __launch_bounds__(kSelThreads) void reduce_select_kernel(
     uint8_t* __restrict__ shot_selected, int32_t* __restrict__ status,
     int32_t* __restrict__ kept_positions) {
   const int p = blockIdx.x, tid = threadIdx.x;
-  const int lane = tid % kWave, wave = tid / kWave;
   const int32_t* off_g = shot_offsets + static_cast<size_t>(p / share) * (n_shots + 1);
   float* scores = shot_scores + static_cast<size_t>(p) * n_shots;
 
   __shared__ int s_off[SHOTKV_MAX_SHOTS + 1];
-  __shared__ int s_a[SHOTKV_MAX_SHOTS + 2];   // shot scores (as float bits) while ranking, then the scan array
+  __shared__ uint64_t s_key[kKeySlots];       // the sort's exchange buffer, then (as ints) the scan array
   __shared__ uint16_t s_idx[SHOTKV_MAX_SHOTS];
   __shared__ uint8_t s_keep[SHOTKV_MAX_SHOTS];
   __shared__ int s_tmp[kSelWaves + 1];
   __shared__ int s_flag;
-  float* s_score = reinterpret_cast<float*>(s_a);
+  int* s_a = reinterpret_cast<int*>(s_key);   // SHOTKV_MAX_SHOTS + 2 ints
+  static_assert(sizeof(uint64_t) * kKeySlots >= sizeof(int) * (SHOTKV_MAX_SHOTS + 2), "scan array fits");
 
   // ---- shot boundaries into LDS, validated: 0 <= off[0], strictly increasing, off[n] <= n_tokens --
   if (tid == 0) s_flag = 0;
@@ -91,22 +167,26 @@ __global__ __launch_bounds__(kSelThreads) void reduce_select_kernel(
   const bool bad = s_flag != 0;
 
   // ---- Eq. 3: one score per shot from the masses of its chunks ----------------------------------
-  if (MASS) {
-    if (!bad) {
-      const float* mass = chunk_mass + static_cast<size_t>(p) * max_c;
-      const int32_t* sf = seg_first + static_cast<size_t>(p) * (n_shots + 3);
-      for (int i = tid; i < n_shots; i += kSelThreads) {
+  // thread tid takes shots tid, tid + 1024, ...: the layout the sort starts from
+  constexpr int kMaxPerThread = kMaxPad / kSelThreads;
+  float my_score[kMaxPerThread];
+#pragma unroll
+  for (int j = 0; j < kMaxPerThread; ++j) {
+    const int i = tid + kSelThreads * j;
+    my_score[j] = 0.f;
+    if (i >= n_shots) continue;
+    if (MASS) {
+      if (!bad) {
+        const float* mass = chunk_mass + static_cast<size_t>(p) * max_c;
+        const int32_t* sf = seg_first + static_cast<size_t>(p) * (n_shots + 3);
         float sum = 0.f;
         for (int c = sf[i + 1]; c < sf[i + 2]; ++c) sum += mass[c];
-        const float sc = sum / static_cast<float>(s_off[i + 1] - s_off[i]);
-        scores[i] = sc;
-        if (SELECT) s_score[i] = sc;
+        my_score[j] = sum / static_cast<float>(s_off[i + 1] - s_off[i]);
       }
-    } else {
-      for (int i = tid; i < n_shots; i += kSelThreads) scores[i] = 0.f;
+      scores[i] = my_score[j];
+    } else if (!bad) {
+      my_score[j] = scores[i];
     }
-  } else if (!bad) {
-    for (int i = tid; i < n_shots; i += kSelThreads) s_score[i] = scores[i];
   }
   if (!SELECT) return;
 
@@ -126,33 +206,37 @@ __global__ __launch_bounds__(kSelThreads) void reduce_select_kernel(
     return;
   }
 
-  // ---- rank: bitonic sort of (score, index) ------------------------------------------------------
-  int n_pad = 1;
+  // ---- rank: sort one key per shot, descending ----------------------------------------------------
+  int n_pad = kWave;
   while (n_pad < n_shots) n_pad <<= 1;
-  for (int i = tid; i < n_pad; i += kSelThreads) {
-    if (i >= n_shots) s_score[i] = -INFINITY;
-    s_idx[i] = static_cast<uint16_t>(i);  // padding carries indices >= n_shots, so it ranks after every real -inf score
-  }
-  __syncthreads();
-  for (int size = 2; size <= n_pad; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      for (int t = tid; t < (n_pad >> 1); t += kSelThreads) {
-        const int lo = ((t / stride) * stride << 1) + (t % stride);
-        const int hi = lo + stride;
-        const bool ascending = ((lo & size) == 0);  // "ascending" = rank order
-        const float sa = s_score[lo], sb = s_score[hi];
-        const int ia = s_idx[lo], ib = s_idx[hi];
-        const bool in_order = ranks_before(sa, ia, sb, ib);
-        if (in_order != ascending) {
-          s_score[lo] = sb; s_score[hi] = sa;
-          s_idx[lo] = static_cast<uint16_t>(ib); s_idx[hi] = static_cast<uint16_t>(ia);
-        }
-      }
-      __syncthreads();
+  {
+    uint64_t key[kMaxPerThread];
+#pragma unroll
+    for (int j = 0; j < kMaxPerThread; ++j) {
+      const int i = tid + kSelThreads * j;
+      key[j] = i < n_shots ? rank_key(my_score[j], i) : padding_key(i);
+    }
+    if (n_pad <= kSelThreads) {
+      uint64_t k1[1] = {key[0]};
+      sort_keys_descending<1>(k1, n_pad, s_key);
+      key[0] = k1[0];
+    } else if (n_pad <= 2 * kSelThreads) {
+      uint64_t k2[2] = {key[0], key[1]};
+      sort_keys_descending<2>(k2, n_pad, s_key);
+      key[0] = k2[0];
+      key[1] = k2[1];
+    } else {
+      sort_keys_descending<kMaxPerThread>(key, n_pad, s_key);
+    }
+#pragma unroll
+    for (int j = 0; j < kMaxPerThread; ++j) {
+      const int r = tid + kSelThreads * j;  // rank
+      if (r < n_shots) s_idx[r] = static_cast<uint16_t>(0xFFFFFFFFu - static_cast<uint32_t>(key[j]));
     }
   }
+  __syncthreads();  // the ranking is complete, and the exchange buffer is free to become the scan array
 
-  // ---- budget walk in rank order (the scores are no longer needed: s_a becomes the scan array) ----
+  // ---- budget walk in rank order ---------------------------------------------------------------------
   for (int i = tid; i < n_shots; i += kSelThreads) {
     const int shot = s_idx[i];
     s_a[i] = s_off[shot + 1] - s_off[shot];
@@ -192,12 +276,20 @@ __global__ __launch_bounds__(kSelThreads) void reduce_select_kernel(
   }
   __syncthreads();
   const int total = block_exclusive_scan(s_a, n_seg, s_tmp);  // s_a[s] = first output row of segment s
-  // every retained row's original position; one wave per segment, lanes along the rows
-  for (int s = wave; s < n_seg; s += kSelWaves) {
+  // every retained row's original position: a group of lanes per segment, lanes along the rows; the
+  // group is as wide as an average shot is long (a wave for shots of hundreds of tokens, 8..32 lanes for
+  // sentence-sized units), so that most lanes have a row to write
+  int group_w = 8;
+  {
+    const int avg = n_shots > 0 ? (s_off[n_shots] - s_off[0]) / n_shots : kWave;
+    while (group_w < kWave && group_w < avg) group_w <<= 1;
+  }
+  const int n_groups = kSelThreads / group_w, gid = tid / group_w, gl = tid % group_w;
+  for (int s = gid; s < n_seg; s += n_groups) {
     int src, len;
     segment(s, src, len);
     const int dst = s_a[s];
-    for (int i = lane; i < len; i += kWave) kept_pos[dst + i] = src + i;
+    for (int i = gl; i < len; i += group_w) kept_pos[dst + i] = src + i;
   }
   if (sel) for (int i = tid; i < n_shots; i += kSelThreads) sel[i] = s_keep[i];
   if (tid == 0) { status[p] = SHOTKV_ST_OK; kept_count[p] = total; }
