@@ -132,6 +132,12 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
       // a block of dead prefill rows only (count below cap) is skipped: its logits are masked between the
       // passes whatever zbuf holds.  A wave's first block is fetched regardless, before the count is known.
       if (blk != wave && t_begin + blk * 32 >= pc && t_begin + blk * 32 + 31 < cap) continue;
+      // so is a block of decode slots none of which holds a token (a pool that is still filling up)
+      if (t_begin + blk * 32 >= cap) {
+        const int tt = blk * 32 + (lane & 31);
+        const bool holds = tt < T && token_valid(t_begin + tt);
+        if (__builtin_amdgcn_ballot_w64(holds) == 0) continue;
+      }
       u32x4 raw[8];
       const int tt0 = blk * 32 + tau;
       if (t_begin + blk * 32 + 31 < cap && blk * 32 + 31 < T) {  // the whole block lies in the prefill cache
@@ -223,25 +229,35 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
     for (int tt0 = grp; tt0 < T; tt0 += kGroups * kVUnroll) {
       float p[kVUnroll][G];
       u32x4 raw[kVUnroll];
+      bool any[kVUnroll], is_new[kVUnroll];
+      bool work = false;
 #pragma unroll
       for (int u = 0; u < kVUnroll; ++u) {
         const int tt = tt0 + u * kGroups;
         const bool inside = tt < T;
         const int ttc = inside ? tt : 0;
-        bool any = false;
+        any[u] = false;
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) {
           p[u][hh] = (inside && hh < n_group) ? zbuf[ttc][hh] : 0.f;  // padding heads carry no weight
-          any = any || p[u][hh] != 0.f;
+          any[u] = any[u] || p[u][hh] != 0.f;
         }
-        const int t = t_begin + ttc;
         // the slot taking the new token: its value row is appended whatever weight the token got
         // (a weight that underflows to zero must not leave a stale row behind for later steps)
-        const bool is_new = inside && t >= cap && (t - cap) == new_slot;
+        is_new[u] = inside && t_begin + ttc >= cap && (t_begin + ttc - cap) == new_slot;
+        work = work || any[u] || is_new[u];
+      }
+      // dead prefill rows and empty decode slots: nothing to fetch, nothing to add
+      if (__builtin_amdgcn_ballot_w64(work) == 0) continue;
+#pragma unroll
+      for (int u = 0; u < kVUnroll; ++u) {
+        const int tt = tt0 + u * kGroups;
+        const int t = t_begin + (tt < T ? tt : 0);
         const bf16_t* vr = v_new + new_off;
-        if (any && !is_new) vr = (t < cap) ? v_prefill + (plane_p + t) * kD : v_dec + (plane_d + (t - cap)) * kD;
+        if (any[u] && !is_new[u])
+          vr = (t < cap) ? v_prefill + (plane_p + t) * kD : v_dec + (plane_d + (t - cap)) * kD;
         raw[u] = stream_load(reinterpret_cast<const u32x4*>(vr + lir * 8));
-        if (is_new) *reinterpret_cast<u32x4*>(v_dec + (plane_d + new_slot) * kD + lir * 8) = raw[u];
+        if (is_new[u]) *reinterpret_cast<u32x4*>(v_dec + (plane_d + new_slot) * kD + lir * 8) = raw[u];
       }
 #pragma unroll
       for (int u = 0; u < kVUnroll; ++u) {
