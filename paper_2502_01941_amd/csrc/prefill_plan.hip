@@ -10,7 +10,8 @@ namespace shotkv {
 
 namespace {
 
-constexpr int kPlanThreads = 256;
+constexpr int kPlanThreads = 1024;
+constexpr int kPlanWaves = kPlanThreads / kWave;
 
 __device__ __forceinline__ void segment_span(const int32_t* off, int n_shots, int n_tokens, int s,
                                              int& start, int& len) {
@@ -45,9 +46,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
   int32_t* s_first = seg_first + static_cast<size_t>(p) * (n_shots + 3);
 
   __shared__ int bad;
-  __shared__ int scan[kPlanThreads];
-  __shared__ int carry;
-  if (tid == 0) { bad = 0; carry = 0; }
+  __shared__ int wave_total[kPlanWaves];
+  if (tid == 0) bad = 0;
   __syncthreads();
 
   // validation: 0 <= off[0], off strictly increasing, off[n] <= n_tokens
@@ -70,6 +70,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
   if (tid == 0) status[p] = SHOTKV_ST_OK;
 
   const int n_seg = n_shots + 2;
+  const int lane = tid % kWave, wave = tid / kWave;
+  int carry = 0;  // chunks of the segments before this tile; the same in every thread
   for (int base = 0; base < n_seg; base += kPlanThreads) {
     const int s = base + tid;
     int start = 0, len = 0, nc = 0;
@@ -77,16 +79,23 @@ __global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
       segment_span(off, n_shots, n_tokens, s, start, len);
       nc = chunks_of(len, chunk_keys);
     }
-    // inclusive Hillis-Steele scan of nc over the tile
-    scan[tid] = nc;
-    __syncthreads();
-    for (int o = 1; o < kPlanThreads; o <<= 1) {
-      const int add = (tid >= o) ? scan[tid - o] : 0;
-      __syncthreads();
-      scan[tid] += add;
-      __syncthreads();
+    // inclusive scan of nc over the tile: lane shuffles inside a wave, wave totals through LDS
+    int incl = nc;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int up = __shfl_up(incl, o, kWave);
+      if (lane >= o) incl += up;
     }
-    const int first = carry + scan[tid] - nc;
+    if (lane == kWave - 1) wave_total[wave] = incl;
+    __syncthreads();
+    int before = 0, tile_total = 0;
+#pragma unroll
+    for (int w = 0; w < kPlanWaves; ++w) {
+      const int t = wave_total[w];
+      if (w < wave) before += t;
+      tile_total += t;
+    }
+    const int first = carry + before + incl - nc;
     if (s < n_seg) {
       s_first[s] = first;
       if (nc > 0) {
@@ -97,9 +106,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
         }
       }
     }
-    __syncthreads();
-    if (tid == kPlanThreads - 1) carry += scan[tid];
-    __syncthreads();
+    carry += tile_total;
+    __syncthreads();  // wave_total is rewritten by the next tile; the chunk table is complete after the last
   }
   if (tid == 0) {
     s_first[n_seg] = carry;

@@ -549,7 +549,7 @@ int score_group_keys(int P, int H_kv, int n_tokens) {
   // times over (about 16K workgroups for a large batch)
   const long total_keys = static_cast<long>(n_tokens) * H_kv * P;
   long keys = (total_keys / 16384L + 255) / 256 * 256;
-  if (keys < 512) keys = 512;
+  if (keys < 256) keys = 256;  // a single layer of a few thousand tokens: more, shorter workgroups
   if (keys > 2048) keys = 2048;
   return static_cast<int>(keys);
 #endif

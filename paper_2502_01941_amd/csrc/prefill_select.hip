@@ -16,6 +16,8 @@
 // run in a fixed order (no atomics), so results are reproducible run to run.
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace shotkv {
 
 namespace {
@@ -70,9 +72,36 @@ __device__ __forceinline__ uint64_t rank_key(float score, int idx) {
 }
 __device__ __forceinline__ uint64_t padding_key(int idx) { return 0xFFFFFFFFu - static_cast<uint32_t>(idx); }
 
-__device__ __forceinline__ uint64_t shuffle_xor64(uint64_t v, int lane_mask) {
-  const uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), lane_mask, kWave);
-  const uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), lane_mask, kWave);
+// Value of lane (own lane ^ MASK), MASK a power of two below 64, without a trip through the LDS pipe:
+// data-parallel-primitive moves inside a row of 16 lanes (1, 2: quad permutations; 4: the mirror of 8
+// lanes followed by the mirror of 4; 8: a rotation of the row by 8), row swaps for 16 and half swaps for 32.
+template <int MASK>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
+  static_assert(MASK == 1 || MASK == 2 || MASK == 4 || MASK == 8 || MASK == 16 || MASK == 32, "one lane bit");
+  if constexpr (MASK == 1) {
+    return __builtin_amdgcn_update_dpp(0u, v, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
+  } else if constexpr (MASK == 2) {
+    return __builtin_amdgcn_update_dpp(0u, v, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+  } else if constexpr (MASK == 4) {
+    const uint32_t m = __builtin_amdgcn_update_dpp(0u, v, 0x141, 0xf, 0xf, false);  // row_half_mirror: lane ^ 7
+    return __builtin_amdgcn_update_dpp(0u, m, 0x1B, 0xf, 0xf, false);               // quad_perm [3,2,1,0]: ^ 3
+  } else if constexpr (MASK == 8) {
+    return __builtin_amdgcn_update_dpp(0u, v, 0x128, 0xf, 0xf, false);  // row_ror:8
+  } else if constexpr (MASK == 16) {
+    // first result: own even rows, the other operand's even rows in the odd rows; second: the odd rows
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return (threadIdx.x & 16) ? r[0] : r[1];
+  } else {
+    // first result: the lower half in both halves; second: the upper half in both
+    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return (threadIdx.x & 32) ? r[0] : r[1];
+  }
+}
+
+template <int MASK>
+__device__ __forceinline__ uint64_t lane_xor64(uint64_t v) {
+  const uint32_t lo = lane_xor<MASK>(static_cast<uint32_t>(v));
+  const uint32_t hi = lane_xor<MASK>(static_cast<uint32_t>(v >> 32));
   return (static_cast<uint64_t>(hi) << 32) | lo;
 }
 
@@ -96,15 +125,28 @@ __device__ void sort_keys_descending(uint64_t (&k)[E], int n_pad, uint64_t* keys
     return ((t & low_mask) << 6) | (t >> hb);
   };
   auto slot = [](int a) { return a + (a >> 6); };
-  auto stage = [&](int size, int stride, int lane_mask, bool in_transposed) {
+  // one compare-exchange step with the partner LANE_MASK lanes away: array distance LANE_MASK in the
+  // natural layout, 64 * LANE_MASK in the transposed one
+  auto stage = [&](int size, auto lane_mask_c, bool in_transposed) {
+    constexpr int LANE_MASK = decltype(lane_mask_c)::value;
+    const int stride = in_transposed ? LANE_MASK << 6 : LANE_MASK;
 #pragma unroll
     for (int j = 0; j < E; ++j) {
       const int a = in_transposed ? transposed(j) : natural(j);
-      const uint64_t other = shuffle_xor64(k[j], lane_mask);
+      const uint64_t other = lane_xor64<LANE_MASK>(k[j]);
       const bool want_max = ((a & size) == 0) == ((a & stride) == 0);
       const bool take = want_max ? other > k[j] : other < k[j];
       k[j] = take ? other : k[j];
     }
+  };
+  // the steps of one merge level whose partners are at most `top` lanes away, widest first
+  auto lane_stages = [&](int size, int top, bool in_transposed) {
+    if (top >= 32) stage(size, std::integral_constant<int, 32>{}, in_transposed);
+    if (top >= 16) stage(size, std::integral_constant<int, 16>{}, in_transposed);
+    if (top >= 8) stage(size, std::integral_constant<int, 8>{}, in_transposed);
+    if (top >= 4) stage(size, std::integral_constant<int, 4>{}, in_transposed);
+    if (top >= 2) stage(size, std::integral_constant<int, 2>{}, in_transposed);
+    stage(size, std::integral_constant<int, 1>{}, in_transposed);
   };
   auto relayout = [&](bool to_transposed) {
 #pragma unroll
@@ -124,10 +166,10 @@ __device__ void sort_keys_descending(uint64_t (&k)[E], int n_pad, uint64_t* keys
   for (int size = 2; size <= n_pad; size <<= 1) {
     if (size > kWave) {
       relayout(true);
-      for (int stride = size >> 1; stride >= kWave; stride >>= 1) stage(size, stride, stride >> 6, true);
+      lane_stages(size, size >> 7, true);   // array distances size/2 .. 64
       relayout(false);
     }
-    for (int stride = min(size >> 1, kWave / 2); stride > 0; stride >>= 1) stage(size, stride, stride, false);
+    lane_stages(size, min(size >> 1, kWave / 2), false);
   }
 }
 
@@ -285,11 +327,21 @@ __global__ __launch_bounds__(kSelThreads) void reduce_select_kernel(
     while (group_w < kWave && group_w < avg) group_w <<= 1;
   }
   const int n_groups = kSelThreads / group_w, gid = tid / group_w, gl = tid % group_w;
-  for (int s = gid; s < n_seg; s += n_groups) {
-    int src, len;
-    segment(s, src, len);
-    const int dst = s_a[s];
-    for (int i = gl; i < len; i += group_w) kept_pos[dst + i] = src + i;
+  constexpr int kSegBatch = 4;  // segments whose LDS lookups are in flight together
+  for (int s0 = gid; s0 < n_seg; s0 += n_groups * kSegBatch) {
+    int src[kSegBatch], len[kSegBatch], dst[kSegBatch];
+#pragma unroll
+    for (int b = 0; b < kSegBatch; ++b) {
+      const int s = s0 + b * n_groups;
+      src[b] = 0; len[b] = 0; dst[b] = 0;
+      if (s < n_seg) {
+        segment(s, src[b], len[b]);
+        dst[b] = s_a[s];
+      }
+    }
+#pragma unroll
+    for (int b = 0; b < kSegBatch; ++b)
+      for (int i = gl; i < len[b]; i += group_w) kept_pos[dst[b] + i] = src[b] + i;
   }
   if (sel) for (int i = tid; i < n_shots; i += kSelThreads) sel[i] = s_keep[i];
   if (tid == 0) { status[p] = SHOTKV_ST_OK; kept_count[p] = total; }
