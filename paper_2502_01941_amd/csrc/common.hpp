@@ -37,6 +37,22 @@ __device__ __forceinline__ T wave_sum(T v) {
   return v;
 }
 
+// Combining a value with the one held 32 (or 16) lanes away without a trip through the LDS pipe: the
+// half swap returns the lower half of the wave in both halves of its first result and the upper half in
+// both halves of the second, the row swap does the same for each pair of 16-lane rows.
+__device__ __forceinline__ float sum_across_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float max_across_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_across_row_pairs(float x) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 __host__ __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Upper bound on the number of chunks one problem can be cut into: every segment (n_shots shots plus

@@ -279,8 +279,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_mfma_kernel(
   for (int hh = 0; hh < G; ++hh)
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      o[hh][e] += __shfl_xor(o[hh][e], 16, kWave);
-      o[hh][e] += __shfl_xor(o[hh][e], 32, kWave);
+      o[hh][e] = sum_across_halves(sum_across_row_pairs(o[hh][e]));
     }
   if (lane < 16) {
 #pragma unroll

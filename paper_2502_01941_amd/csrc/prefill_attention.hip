@@ -191,7 +191,7 @@ __global__ __launch_bounds__(kThreadsQ, 2) void attention_scores_kernel(
   float* part_row = partial + static_cast<size_t>(p) * max_c * H_kv * R + static_cast<size_t>(g) * R +
                     h_local * W + win_j;  // + chunk * H_kv * R
   auto finish_chunk = [&]() {
-    const float tot = l_chunk + __shfl_xor(l_chunk, 32, kWave);
+    const float tot = sum_across_halves(l_chunk);
     if (lane_emits)
       part_row[static_cast<size_t>(cur_c) * H_kv * R] = tot > 0.f ? m_run + __builtin_amdgcn_logf(tot) : -INFINITY;
     l_chunk = 0.f;
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(kThreadsQ, 2) void attention_scores_kernel(
       float bm = fmaxf(acc[0], acc[1]);
 #pragma unroll
       for (int v = 2; v < 16; v += 2) bm = fmaxf(fmaxf(bm, acc[v]), acc[v + 1]);
-      bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));
+      bm = max_across_halves(bm);
       const float m_new = fmaxf(m_run, bm * c);  // finite from the first block on: key 0 is always visible
       if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 from -inf
@@ -306,7 +306,7 @@ __global__ __launch_bounds__(kThreadsQ, 2) void attention_scores_kernel(
   }
 
   // ---- results -------------------------------------------------------------------------------------
-  const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+  const float l_tot = sum_across_halves(l_run);
   if (wave_emits) {
     // chunks that reach past this tile's keys hold what their visible part gave; later ones nothing
     while (cur_c < nc) finish_chunk();

@@ -121,7 +121,7 @@ __device__ __forceinline__ void softmax_fold(floatx16 acc, float c, int half, in
   float bm = fmaxf(acc[0], acc[1]);
 #pragma unroll
   for (int v = 2; v < 16; v += 2) bm = fmaxf(fmaxf(bm, acc[v]), acc[v + 1]);
-  bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));
+  bm = max_across_halves(bm);
   const float m_new = fmaxf(m_run, bm * c);
   const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
   const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
@@ -198,7 +198,7 @@ __device__ __forceinline__ void weights_block(lds_cchar* lds_buf, const bf16x8 (
     float bm = fmaxf(e[q][0], e[q][1]);
 #pragma unroll
     for (int v = 2; v < 16; v += 2) bm = fmaxf(fmaxf(bm, e[q][v]), e[q][v + 1]);
-    bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));
+    bm = max_across_halves(bm);
     const float m_new = fmaxf(m_run[q], bm * c);
     const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(m_run[q] - m_safe);
@@ -460,7 +460,7 @@ score_partials_mfma_kernel(
     float val[NQW];
 #pragma unroll
     for (int q = 0; q < NQW; ++q) {
-      const float l = l_run[q] + __shfl_xor(l_run[q], 32, kWave);
+      const float l = sum_across_halves(l_run[q]);
       // log2(0) = -inf: a query that saw none of the chunk's keys; so is a padding query row
       val[q] = (l > 0.f && (qb0 + q) * 32 + (lane & 31) < n_rows) ? m_run[q] + __builtin_amdgcn_logf(l)
                                                                    : -INFINITY;
