@@ -30,7 +30,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `rocprofv3 --pmc` runs of this file, see profiles/score_partials_mfma_model32k_counters.md).  Valid only
 # for the kernel source it was measured on: reported as null once that file's hash differs.
 SCORE_KERNEL_SOURCE = os.path.join(ROOT, "paper_2502_01941_amd", "csrc", "prefill_score_mfma.hip")
-MEASURED_TRAFFIC = {"model32k": {"sha256": "b4ad8361c523cbb594f2ddd1b6edb7821058d3144780d50f78781e9180a9be09",
+MEASURED_TRAFFIC = {"model32k": {"sha256": "c47e800866cfa26fb957fa8ce8a91203711c352e8e642ef93be0735bcda9146e",
                                  "bytes": 8.96e9}}
 
 PREFILL_KINDS = ("plan", "score", "row_stats", "chunk_mass", "reduce_select", "compact")

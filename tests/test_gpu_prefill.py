@@ -200,6 +200,40 @@ def test_select_and_compact_synthetic_scores(kv, mode):
         np.testing.assert_array_equal(helpers.bits(res.v_out[p, :, :kept]), helpers.bits(v[p][:, idx]))
 
 
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 127, 129, 1000, 1023, 1024, 1025, 2047, 2049, 4095, 4096])
+def test_ranking_sizes_and_special_scores(kv, n):
+    """The ranking at every size class of the sorting network (one, two and four keys per thread; with and
+    without the transposed passes; padding of 0..n_pad-1 entries), on scores with heavy ties, both zeros,
+    negative values, infinities and denormals: selection and positions bit-exact against the oracle."""
+    P, H, Hkv, D, W = 4, 2, 1, 128, 8
+    N = 3 * n + 300
+    _, k, v, off = _ragged_problem(P, H, Hkv, D, W, N, torch.bfloat16, 500 + n, n, 2, 40)
+    rng = np.random.default_rng(900 + n)
+    scores = rng.standard_normal((P, n)).astype(np.float32)
+    scores[1] = np.round(scores[1] * 2) / 2                          # heavy ties, +0.0 and -0.0 among them
+    scores[2] = rng.choice(np.array([0.0, -0.0, 1.0, -1.0, np.inf, -np.inf, 1e-42, -1e-42, 3.5],
+                                    dtype=np.float32), size=n)
+    scores[3] = -np.abs(scores[3])                                   # all negative
+    offs = off.cpu().numpy()
+    always = offs[:, 0] + N - offs[:, -1]                            # tokens outside every shot
+    in_shots = offs[:, -1] - offs[:, 0]
+    budgets = (always + in_shots // np.array([2, 3, 2, 1])).astype(np.int32)
+    for mode in (orc.SELECT_PREFIX, orc.SELECT_FIRST_FIT):
+        res = kv.select_and_compact(torch.from_numpy(scores).cuda(), k, v, off, torch.from_numpy(budgets).cuda(),
+                                    N, H, W, mode)
+        torch.cuda.synchronize()
+        assert res.status.cpu().tolist() == [orc.STATUS_OK] * P
+        for p in range(P):
+            n_always = int(offs[p, 0]) + N - int(offs[p, -1])
+            keep = orc.select_shots(scores[p], np.diff(offs[p]), int(budgets[p]) - n_always, mode)
+            assert res.shot_selected[p].cpu().numpy().tolist() == keep.tolist(), (mode, p)
+            pos = orc.kept_positions_from_mask(keep, offs[p], N)
+            kept = res.kept_count[p].item()
+            np.testing.assert_array_equal(res.kept_positions[p, :kept].cpu().numpy(), pos)
+            idx = torch.from_numpy(pos).long().cuda()
+            np.testing.assert_array_equal(helpers.bits(res.k_out[p, :, :kept]), helpers.bits(k[p][:, idx]))
+
+
 def test_many_shots_selection(kv):
     """Sentence-sized units: thousands of short spans stress the sort, the scans and the copy plan."""
     P, H, Hkv, D, W, N, n = 2, 8, 2, 128, 32, 40000, 3000
@@ -240,6 +274,28 @@ def test_maximum_number_of_shots_end_to_end(kv):
     check_prefill_problem(res, 0, q[0], k[0], v[0], off, budget, budget, 1.0 / math.sqrt(D))
     with pytest.raises(kv.ShotKVError):          # one more shot than the library takes
         kv.prefill_scores(q, k, torch.zeros((1, n + 2), dtype=torch.int32, device="cuda"), 0.1)
+
+
+@pytest.mark.parametrize("H,Hkv", [(8, 2), (4, 2), (2, 2), (12, 2), (16, 2)])
+def test_units_of_one_to_three_tokens(kv, H, Hkv):
+    """Units of one to three tokens: up to thirty-two chunk boundaries inside one 32-key block, at every
+    element position of both lane halves, for one to four query blocks per wave (G = 4, 2, 1, 6, 8)."""
+    P, D, W, N, n = 2, 128, 32, 2100, 1000
+    g = torch.Generator(device="cuda").manual_seed(4242 + H)
+    q = torch.randn((P, H, W, D), generator=g, device="cuda").to(torch.bfloat16)
+    k = torch.randn((P, Hkv, N, D), generator=g, device="cuda").to(torch.bfloat16)
+    v = torch.randn((P, Hkv, N, D), generator=g, device="cuda").to(torch.bfloat16)
+    rng = np.random.default_rng(4242 + H)
+    off = np.stack([np.concatenate([[s0], s0 + np.cumsum(rng.integers(1, 4, size=n))]).astype(np.int32)
+                    for s0 in (0, 5)])
+    assert off.max() < N - W
+    budget = N // 3
+    bud = torch.full((P,), budget, dtype=torch.int32, device="cuda")
+    scale = 1.0 / math.sqrt(D)
+    res = kv.prefill_compress(q, k, v, torch.from_numpy(off).cuda(), bud, budget, scale)
+    torch.cuda.synchronize()
+    for p in range(P):
+        check_prefill_problem(res, p, q[p], k[p], v[p], off[p], budget, budget, scale)
 
 
 def test_inputs_are_not_modified_and_runs_repeat_bitwise(kv):
