@@ -108,7 +108,8 @@ struct PrefillWorkspace {
   float*   row_stat;      // [P][H_kv][R]  log2 of the row's sum of exponentials over all chunks
   float*   chunk_mass;    // [P][maxC]
   float*   scores;        // [P][n_shots]
-  void*    vt;            // fused attention path only: V packed into 32-key blocks [P][H_kv][blocks][D][32]
+  void*    vt;            // fused attention path only: V packed into 32-key blocks [P][H_kv][blocks][D][32], fp16
+  uint32_t* v_absmax;     // fused attention path only: [P][H_kv] largest finite |v| of the plane, as bf16 bits
   int32_t  max_c;
   int32_t  chunk_keys;
   int32_t  group_keys;    // keys per slice of the key axis, 0 on the generic path
@@ -146,6 +147,7 @@ inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_
   w.chunk_mass = reinterpret_cast<float*>(take(P_ * C * 4));
   w.scores = reinterpret_cast<float*>(take(P_ * S * 4 + 4));
   w.vt = vt_bytes ? take(vt_bytes) : nullptr;
+  w.v_absmax = vt_bytes ? reinterpret_cast<uint32_t*>(take(P_ * H_kv * 4)) : nullptr;
   w.bytes = off;
   return w;
 }
@@ -184,7 +186,7 @@ bool score_uses_mfma(const PrefillDims& d);
 // causal attention forward that also writes the window rows' softmax partials and row denominators
 bool attention_supported(const PrefillDims& d);
 int attention_key_blocks(int n_tokens);
-hipError_t launch_pack_vt(const PrefillDims& d, const void* v, void* vt, hipStream_t s);
+hipError_t launch_pack_vt(const PrefillDims& d, const void* v, const PrefillWorkspace& w, hipStream_t s);
 hipError_t launch_attention_scores(const PrefillDims& d, const void* q, const void* k, const void* vt,
                                    float* attn_out, const PrefillWorkspace& w, hipStream_t s);
 

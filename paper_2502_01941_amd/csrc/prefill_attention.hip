@@ -18,8 +18,14 @@
 //                     rescaling the output is a per-lane multiply.  The A operand needs V with keys
 //                     contiguous; a small pre-pass packs V once into 32-key blocks [d][key] in exactly the
 //                     key order the accumulator registers have.
-//   precision         weights are fed to the matrix cores as bf16 hi + bf16 lo (two instructions), so
-//                     the output carries fp32-level weights; sums of weights are kept in fp32.
+//   precision         this product runs in fp16 (v_mfma_f32_32x32x16_f16): a weight keeps 11 significant bits
+//                     instead of bf16's 8, which holds the output within 4e-4 of its row maximum with one
+//                     instruction per step (a bf16 weight is off by up to 2^-9; bf16 hi + lo would cost a
+//                     second instruction).  fp16's narrow range is dealt with by two exact power-of-two
+//                     scalings: the softmax reference sits 15 below the running maximum, so weights lie
+//                     in (0, 2^15] and anything above 2^-39 of the largest survives; and the pre-pass
+//                     scales every KV-head plane of V so that its largest finite |v| lands in [2^14, 2^15).
+//                     Sums of weights stay in fp32 and carry the same reference.
 // K and packed-V blocks are streamed global -> LDS with direct-to-LDS loads into a ring of three stages
 // shared by the four waves (one barrier per block); the LDS layouts are bank-conflict free for the
 // 128-bit operand reads (K as in the score kernel; V^T rows of 64 bytes with a two-bit XOR of the
@@ -32,17 +38,22 @@ namespace shotkv {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(2))) float floatx2;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((address_space(3))) const char lds_cchar;
 typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
+typedef __attribute__((address_space(3))) const f16x8 lds_f16x8;
 
 constexpr int kD = 128;
 constexpr int kBlockKeys = 32;
 constexpr int kRowBytes = kD * 2;
 constexpr int kGroupBytes = 4 * kRowBytes + 64;       // K: four rows + pad = one direct-to-LDS instruction
 constexpr int kKBytes = 8 * kGroupBytes;              // 8704
-constexpr int kVtBytes = kD * kBlockKeys * 2;         // 8192: [128 d][32 keys] bf16
+constexpr int kVtBytes = kD * kBlockKeys * 2;         // 8192: [128 d][32 keys] fp16
+constexpr int kWeightShift = 15;                      // softmax reference = running maximum - 15 (log2 domain)
 constexpr int kStageBytes = kKBytes + kVtBytes;
 constexpr int kRing = 3;
 constexpr int kTileQ = 128;
@@ -51,28 +62,63 @@ constexpr int kThreadsQ = kWavesQ * kWave;
 constexpr int kLoadsPerWave = 4;                      // 2 K groups + 2 V^T slabs per wave per block
 
 // ---- V packing -----------------------------------------------------------------------------------
-// vt[p][g][block][d][c][j] = V[p][g][32*block + 8*(2*(c/2) + j/4) + 4*(c%2) + j%4][d]: column c = 2*s + half
-// holds, in order, the eight keys whose weights a lane of half `half` feeds to matrix step s.  Keys past
-// n_tokens are zero.
+// Largest finite |v| of every KV-head plane, as bf16 bits (their order is the order of the magnitudes),
+// collected with atomic maxima into v_absmax, which the planning kernel has set to zero.
+__global__ __launch_bounds__(256) void v_absmax_kernel(const bf16_t* __restrict__ v, int n_tokens,
+                                                       uint32_t* __restrict__ v_absmax) {
+  const size_t plane = blockIdx.y;
+  const size_t n16 = static_cast<size_t>(n_tokens) * kD / 8;  // 16-byte pieces of the plane
+  const u32x4* src = reinterpret_cast<const u32x4*>(v + plane * n_tokens * kD);
+  uint32_t best = 0u;
+  for (size_t i = static_cast<size_t>(blockIdx.x) * 2048 + threadIdx.x; i < min(n16, (static_cast<size_t>(blockIdx.x) + 1) * 2048);
+       i += 256) {
+    const u32x4 raw = src[i];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t lo = raw[e] & 0x7fffu, hi = (raw[e] >> 16) & 0x7fffu;
+      if (lo < 0x7f80u) best = max(best, lo);  // infinities and NaNs do not set the scale
+      if (hi < 0x7f80u) best = max(best, hi);
+    }
+  }
+  best = wave_max(best);
+  if (threadIdx.x % kWave == 0 && best != 0u) atomicMax(v_absmax + plane, best);
+}
+
+// The power of two that brings a plane's largest |v| (bf16 bits) into [2^14, 2^15): multiply V by
+// plane_scale(bits, false) when packing, the output by plane_scale(bits, true).  Both are exact.
+__device__ __forceinline__ float plane_scale(uint32_t absmax_bits, bool inverse) {
+  int e = static_cast<int>(absmax_bits >> 7);  // biased exponent of the largest magnitude
+  e = min(max(e, 15), 254);                    // all-zero, denormal or absurdly small planes: a fixed scale
+  return __uint_as_float(static_cast<uint32_t>(inverse ? e - 14 : 268 - e) << 23);
+}
+
+// vt[p][g][block][d][c][j] = scale * V[p][g][32*block + 8*(2*(c/2) + j/4) + 4*(c%2) + j%4][d] as fp16: column
+// c = 2*s + half holds, in order, the eight keys whose weights a lane of half `half` feeds to matrix step s.
+// Keys past n_tokens are zero.
 __global__ __launch_bounds__(256) void pack_vt_kernel(const bf16_t* __restrict__ v, int n_tokens, int n_blocks,
-                                                      bf16_t* __restrict__ vt) {
+                                                      const uint32_t* __restrict__ v_absmax,
+                                                      uint16_t* __restrict__ vt) {
   const int blk = blockIdx.x;
   const size_t plane = blockIdx.y;  // p * H_kv + g
-  __shared__ bf16_t tile[kBlockKeys][kD + 2];
+  __shared__ uint16_t tile[kBlockKeys][kD + 2];
+  const float scale = plane_scale(v_absmax[plane], false);
   const bf16_t* src = v + plane * n_tokens * kD;
   for (int i = threadIdx.x; i < kBlockKeys * kD / 8; i += 256) {
     const int key = i / (kD / 8), d8 = i % (kD / 8);
     const int t = blk * kBlockKeys + key;
     u32x4 raw = {0u, 0u, 0u, 0u};
-    if (t < n_tokens) raw = *reinterpret_cast<const u32x4*>(src + static_cast<size_t>(t) * kD + d8 * 8);
+    if (t < n_tokens) raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + static_cast<size_t>(t) * kD + d8 * 8));
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      tile[key][d8 * 8 + 2 * e] = static_cast<bf16_t>(raw[e] & 0xffffu);
-      tile[key][d8 * 8 + 2 * e + 1] = static_cast<bf16_t>(raw[e] >> 16);
+      const floatx2 f = {__uint_as_float(raw[e] << 16) * scale, __uint_as_float(raw[e] & 0xffff0000u) * scale};
+      const f16x2 hh = __builtin_convertvector(f, f16x2);
+      const uint32_t bits = __builtin_bit_cast(uint32_t, hh);
+      tile[key][d8 * 8 + 2 * e] = static_cast<uint16_t>(bits & 0xffffu);
+      tile[key][d8 * 8 + 2 * e + 1] = static_cast<uint16_t>(bits >> 16);
     }
   }
   __syncthreads();
-  bf16_t* dst = vt + (plane * n_blocks + blk) * (kD * kBlockKeys);
+  uint16_t* dst = vt + (plane * n_blocks + blk) * (kD * kBlockKeys);
   for (int i = threadIdx.x; i < kD * 4; i += 256) {  // one 16-byte column per thread
     const int d = i / 4, c = i % 4, s = c >> 1, half = c & 1;
     uint32_t w[4];
@@ -121,16 +167,21 @@ __device__ __forceinline__ void issue_vt(const char* __restrict__ vt_block, uint
   }
 }
 
-__device__ __forceinline__ bf16x8 to_bf16x8(const float (&x)[8]) {
-  bf16x8 r;
+__device__ __forceinline__ f16x8 to_f16x8(const float* x) {
+  f16x8 r;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) r[j] = static_cast<__bf16>(x[j]);
+  for (int j = 0; j < 8; j += 2) {
+    const floatx2 f = {x[j], x[j + 1]};
+    const f16x2 hh = __builtin_convertvector(f, f16x2);  // round to nearest even
+    r[j] = hh[0];
+    r[j + 1] = hh[1];
+  }
   return r;
 }
 
 __global__ __launch_bounds__(kThreadsQ, 2) void attention_scores_kernel(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ vt, int n_tokens,
-    int n_blocks_total, int H, int H_kv, int W, float c, float* __restrict__ o_out,
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const uint16_t* __restrict__ vt,
+    const uint32_t* __restrict__ v_absmax, int n_tokens, int n_blocks_total, int H, int H_kv, int W, float c, float* __restrict__ o_out,
     const int32_t* __restrict__ n_chunks, const int32_t* __restrict__ chunk_start,
     const int32_t* __restrict__ chunk_len, int max_c, int R, float* __restrict__ partial,
     float* __restrict__ row_stat) {
@@ -238,7 +289,9 @@ __global__ __launch_bounds__(kThreadsQ, 2) void attention_scores_kernel(
 #pragma unroll
       for (int v = 2; v < 16; v += 2) bm = fmaxf(fmaxf(bm, acc[v]), acc[v + 1]);
       bm = max_across_halves(bm);
-      const float m_new = fmaxf(m_run, bm * c);  // finite from the first block on: key 0 is always visible
+      // the reference sits kWeightShift below the largest logit: weights up to 2^15, well inside fp16, and
+      // small ones far from its underflow.  Finite from the first block on: key 0 is always visible
+      const float m_new = fmaxf(m_run, fmaf(bm, c, -static_cast<float>(kWeightShift)));
       if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 from -inf
         l_run *= alpha;
@@ -277,29 +330,18 @@ __global__ __launch_bounds__(kThreadsQ, 2) void attention_scores_kernel(
         else break;
       }
     }
-    // ---- O^T += V_blk^T P^T, weights as bf16 hi + lo ----------------------------------------------
+    // ---- O^T += V_blk^T P^T in fp16 -------------------------------------------------------------------
     if (has_work) {
       lds_cchar* vblk = lds_base + slot * kStageBytes + kKBytes;
-      bf16x8 p_hi[2], p_lo[2];
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        float x[8], r[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) x[j] = pw[8 * s + j];
-        p_hi[s] = to_bf16x8(x);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) r[j] = x[j] - static_cast<float>(p_hi[s][j]);
-        p_lo[s] = to_bf16x8(r);
-      }
+      const f16x8 p16[2] = {to_f16x8(pw), to_f16x8(pw + 8)};
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         const int d = 32 * t + (lane & 31);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
           const int col = (2 * s + half) ^ ((d >> 2) & 3);
-          const bf16x8 a = *reinterpret_cast<lds_bf16x8*>(vblk + d * 64 + col * 16);
-          ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_hi[s], ot[t], 0, 0, 0);
-          ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_lo[s], ot[t], 0, 0, 0);
+          const f16x8 a = *reinterpret_cast<lds_f16x8*>(vblk + d * 64 + col * 16);
+          ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p16[s], ot[t], 0, 0, 0);
         }
       }
     }
@@ -315,13 +357,16 @@ __global__ __launch_bounds__(kThreadsQ, 2) void attention_scores_kernel(
   }
   if (q_row < n_tokens) {
     const float inv = 1.f / l_tot;
+    // undoes V's scale; applied after the normalisation, because up / l_tot can fall below the normal range
+    const float up = plane_scale(v_absmax[static_cast<size_t>(p) * H_kv + g], true);
     float* dst = o_out + ((static_cast<size_t>(p) * H + h) * n_tokens + q_row) * kD + 4 * half;
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
       for (int a = 0; a < 4; ++a)
         *reinterpret_cast<float4*>(dst + 32 * t + 8 * a) =
-            make_float4(ot[t][4 * a] * inv, ot[t][4 * a + 1] * inv, ot[t][4 * a + 2] * inv, ot[t][4 * a + 3] * inv);
+            make_float4(ot[t][4 * a] * inv * up, ot[t][4 * a + 1] * inv * up, ot[t][4 * a + 2] * inv * up,
+                        ot[t][4 * a + 3] * inv * up);
   }
 }
 
@@ -334,11 +379,14 @@ bool attention_supported(const PrefillDims& d) {
 
 int attention_key_blocks(int n_tokens) { return ceil_div(n_tokens, kBlockKeys); }
 
-hipError_t launch_pack_vt(const PrefillDims& d, const void* v, void* vt, hipStream_t s) {
+hipError_t launch_pack_vt(const PrefillDims& d, const void* v, const PrefillWorkspace& w, hipStream_t s) {
   const int nb = attention_key_blocks(d.n_tokens);
   KernelTimer timer(d.timing, kKernelPackVt, s);
+  const int pieces = ceil_div(d.n_tokens * (kD / 8), 2048);  // 2048 16-byte pieces (128 rows) per workgroup
+  hipLaunchKernelGGL(v_absmax_kernel, dim3(pieces, d.P * d.H_kv), dim3(256), 0, s, static_cast<const bf16_t*>(v),
+                     d.n_tokens, w.v_absmax);
   hipLaunchKernelGGL(pack_vt_kernel, dim3(nb, d.P * d.H_kv), dim3(256), 0, s, static_cast<const bf16_t*>(v),
-                     d.n_tokens, nb, static_cast<bf16_t*>(vt));
+                     d.n_tokens, nb, w.v_absmax, static_cast<uint16_t*>(w.vt));
   return hipGetLastError();
 }
 
@@ -348,7 +396,8 @@ hipError_t launch_attention_scores(const PrefillDims& d, const void* q, const vo
   const dim3 grid(d.H, d.P, ceil_div(d.n_tokens, kTileQ));
   KernelTimer timer(d.timing, kKernelAttention, s);
   hipLaunchKernelGGL(attention_scores_kernel, grid, dim3(kThreadsQ), 0, s, static_cast<const bf16_t*>(q),
-                     static_cast<const bf16_t*>(k), static_cast<const bf16_t*>(vt), d.n_tokens, nb, d.H, d.H_kv,
+                     static_cast<const bf16_t*>(k), static_cast<const uint16_t*>(vt), w.v_absmax, d.n_tokens, nb, d.H,
+                     d.H_kv,
                      d.W, d.sm_scale * kLog2e, attn_out, w.n_chunks, w.chunk_start, w.chunk_len, w.max_c, d.R,
                      w.partial, w.row_stat);
   return hipGetLastError();

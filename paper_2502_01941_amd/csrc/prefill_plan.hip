@@ -37,7 +37,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
     const int32_t* __restrict__ shot_offsets, int share, int n_shots, int n_tokens, int chunk_keys, int max_c,
     int32_t* __restrict__ status, int32_t* __restrict__ n_chunks, int32_t* __restrict__ chunk_start,
     int32_t* __restrict__ chunk_len, int32_t* __restrict__ seg_first, int group_keys, int n_groups,
-    int32_t* __restrict__ group_first) {
+    int32_t* __restrict__ group_first, uint32_t* __restrict__ v_absmax, int n_kv_heads) {
   const int p = blockIdx.x;
   const int tid = threadIdx.x;
   const int32_t* off = shot_offsets + static_cast<size_t>(p / share) * (n_shots + 1);
@@ -48,6 +48,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_chunks_kernel(
   __shared__ int bad;
   __shared__ int wave_total[kPlanWaves];
   if (tid == 0) bad = 0;
+  // the fused attention path collects the largest |v| of every KV-head plane with atomic maxima: start at 0
+  if (v_absmax && tid < n_kv_heads) v_absmax[static_cast<size_t>(p) * n_kv_heads + tid] = 0u;
   __syncthreads();
 
   // validation: 0 <= off[0], off strictly increasing, off[n] <= n_tokens
@@ -133,7 +135,7 @@ hipError_t launch_plan_chunks(const PrefillDims& d, const int32_t* shot_offsets,
   KernelTimer timer(d.timing, kKernelPlan, s);
   hipLaunchKernelGGL(plan_chunks_kernel, dim3(d.P), dim3(kPlanThreads), 0, s, shot_offsets, d.share, d.n_shots,
                      d.n_tokens, w.chunk_keys, w.max_c, status, w.n_chunks, w.chunk_start, w.chunk_len,
-                     w.seg_first, w.group_keys, w.n_groups, w.group_first);
+                     w.seg_first, w.group_keys, w.n_groups, w.group_first, w.v_absmax, d.H_kv);
   return hipGetLastError();
 }
 

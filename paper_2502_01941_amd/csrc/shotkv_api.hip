@@ -249,7 +249,7 @@ int shotkv_prefill_attention_compress(const shotkv_config* cfg, int32_t P, int32
   float* scores = shot_scores ? shot_scores : w.scores;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = launch_plan_chunks(d, shot_offsets, status, w, s);
-  if (e == hipSuccess) e = launch_pack_vt(d, v, w.vt, s);
+  if (e == hipSuccess) e = launch_pack_vt(d, v, w, s);
   if (e == hipSuccess) e = launch_attention_scores(d, q, k, w.vt, attn_out, w, s);
   if (e == hipSuccess) e = launch_chunk_mass(d, w, s);
   if (e == hipSuccess)

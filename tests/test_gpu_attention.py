@@ -11,7 +11,7 @@ from paper_2502_01941_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-OUT_TOL = 1e-3        # |dO| <= OUT_TOL * max|O| per query row (weights reach the matrix cores as bf16 hi + lo)
+OUT_TOL = 1e-3        # |dO| <= OUT_TOL * max|O| per query row (weights reach the matrix cores with 11 significant bits)
 
 
 @pytest.fixture(scope="module")
@@ -74,6 +74,44 @@ def test_attention_and_compression_match_the_oracle(kv, H, H_kv, W, N, n_shots, 
     torch.cuda.synchronize()
     np.testing.assert_allclose(res.shot_scores.cpu().numpy(), res2.shot_scores.cpu().numpy(), rtol=2e-5)
     assert torch.equal(res.shot_selected, res2.shot_selected) and torch.equal(res.kept_count, res2.kept_count)
+
+
+@pytest.mark.parametrize("factors", [(1e-30, 1.0), (3e4, 1e30), (2.0 ** -120, 2.0 ** 100), (0.0, 1.0)])
+def test_value_magnitudes(kv, factors):
+    """The weighted-value product runs in fp16 behind an exact per-plane power-of-two scale: value planes
+    of very different magnitudes (one factor per KV head, an all-zero plane among them) keep the same
+    relative accuracy."""
+    H, H_kv, W, N, n_shots, budget = 4, 2, 16, 900, 5, 450
+    shape = wl.PrefillShape("attn", 1, H, H_kv, 128, W, N, n_shots, torch.bfloat16, budget, len_lo=90, len_hi=150)
+    q, q_obs, k, v, off, bud = _problem_batch(shape, 33)
+    v = (v.float() * torch.tensor(factors, device="cuda").view(1, H_kv, 1, 1)).to(torch.bfloat16)
+    attn, res = kv.prefill_attention_compress(q, k, v, off, bud, budget, W, shape.sm_scale)
+    torch.cuda.synchronize()
+    assert torch.isfinite(attn).all()
+    ref = orc.causal_attention(to_np(q[0]), to_np(k[0]), to_np(v[0]), shape.sm_scale)
+    got = attn[0].cpu().numpy().astype(np.float64)
+    bound = OUT_TOL * np.abs(ref).max(axis=2, keepdims=True)
+    assert np.all(np.abs(got - ref) <= bound), np.abs(got - ref).max()
+    check_prefill_problem(res, 0, q_obs[0], k[0], v[0], off[0].cpu().numpy(), budget, budget, shape.sm_scale)
+
+
+def test_flat_and_peaked_rows(kv):
+    """Rows whose weights are all equal (zero queries: the output is the running mean of V, thousands of
+    weights of 2^-11 of the total each) next to rows with one dominating key."""
+    H, H_kv, W, N, n_shots, budget = 4, 2, 16, 3000, 6, 1500
+    shape = wl.PrefillShape("attn", 1, H, H_kv, 128, W, N, n_shots, torch.bfloat16, budget, len_lo=300, len_hi=450)
+    q, q_obs, k, v, off, bud = _problem_batch(shape, 34)
+    q[0, 0] = 0                                   # head 0: uniform attention at every position
+    q[0, 1] = (k[0, 0] * 4).to(q.dtype)           # head 1: every position attends to itself almost exclusively
+    q_obs = q[:, :, N - W:].contiguous()
+    attn, res = kv.prefill_attention_compress(q, k, v, off, bud, budget, W, shape.sm_scale)
+    torch.cuda.synchronize()
+    vh = to_np(v[0]).astype(np.float64)
+    mean = np.cumsum(vh[0], axis=0) / np.arange(1, N + 1)[:, None]
+    got = attn[0].cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got[0] - mean) <= OUT_TOL * np.abs(mean).max(axis=1, keepdims=True))
+    _check_rows(attn[0], q[0], k[0], v[0], [0, 5, 100, 1023, 2047, N - 1], shape.sm_scale)
+    check_prefill_problem(res, 0, q_obs[0], k[0], v[0], off[0].cpu().numpy(), budget, budget, shape.sm_scale)
 
 
 def test_layer8k_fused(kv):
