@@ -68,20 +68,34 @@ __global__ __launch_bounds__(256) void v_absmax_kernel(const bf16_t* __restrict_
                                                        uint32_t* __restrict__ v_absmax) {
   const size_t plane = blockIdx.y;
   const size_t n16 = static_cast<size_t>(n_tokens) * kD / 8;  // 16-byte pieces of the plane
+  const size_t per = (n16 + gridDim.x - 1) / gridDim.x;       // a contiguous share per workgroup
+  const size_t lo = blockIdx.x * per, hi = min(n16, lo + per);
   const u32x4* src = reinterpret_cast<const u32x4*>(v + plane * n_tokens * kD);
   uint32_t best = 0u;
-  for (size_t i = static_cast<size_t>(blockIdx.x) * 2048 + threadIdx.x; i < min(n16, (static_cast<size_t>(blockIdx.x) + 1) * 2048);
-       i += 256) {
-    const u32x4 raw = src[i];
+  auto fold = [&](const u32x4& raw) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const uint32_t lo = raw[e] & 0x7fffu, hi = (raw[e] >> 16) & 0x7fffu;
-      if (lo < 0x7f80u) best = max(best, lo);  // infinities and NaNs do not set the scale
-      if (hi < 0x7f80u) best = max(best, hi);
+      const uint32_t a = raw[e] & 0x7fffu, b = (raw[e] >> 16) & 0x7fffu;
+      if (a < 0x7f80u) best = max(best, a);  // infinities and NaNs do not set the scale
+      if (b < 0x7f80u) best = max(best, b);
     }
+  };
+  size_t i = lo + threadIdx.x;
+  for (; i + 3 * 256 < hi; i += 4 * 256) {  // four loads in flight per thread
+    const u32x4 r0 = src[i], r1 = src[i + 256], r2 = src[i + 512], r3 = src[i + 768];
+    fold(r0); fold(r1); fold(r2); fold(r3);
   }
+  for (; i < hi; i += 256) fold(src[i]);
+  // one atomic per workgroup: a few dozen per plane, not thousands on one address
+  __shared__ uint32_t wave_best[256 / kWave];
   best = wave_max(best);
-  if (threadIdx.x % kWave == 0 && best != 0u) atomicMax(v_absmax + plane, best);
+  if (threadIdx.x % kWave == 0) wave_best[threadIdx.x / kWave] = best;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < 256 / kWave; ++w) best = max(best, wave_best[w]);
+    if (best != 0u) atomicMax(v_absmax + plane, best);
+  }
 }
 
 // The power of two that brings a plane's largest |v| (bf16 bits) into [2^14, 2^15): multiply V by
@@ -382,8 +396,10 @@ int attention_key_blocks(int n_tokens) { return ceil_div(n_tokens, kBlockKeys); 
 hipError_t launch_pack_vt(const PrefillDims& d, const void* v, const PrefillWorkspace& w, hipStream_t s) {
   const int nb = attention_key_blocks(d.n_tokens);
   KernelTimer timer(d.timing, kKernelPackVt, s);
-  const int pieces = ceil_div(d.n_tokens * (kD / 8), 2048);  // 2048 16-byte pieces (128 rows) per workgroup
-  hipLaunchKernelGGL(v_absmax_kernel, dim3(pieces, d.P * d.H_kv), dim3(256), 0, s, static_cast<const bf16_t*>(v),
+  // enough workgroups to fill the chip a few times over, each with at least 128 rows of a plane
+  const int planes = d.P * d.H_kv;
+  const int shares = max(1, min(ceil_div(d.n_tokens, 128), ceil_div(1024, planes)));
+  hipLaunchKernelGGL(v_absmax_kernel, dim3(shares, planes), dim3(256), 0, s, static_cast<const bf16_t*>(v),
                      d.n_tokens, w.v_absmax);
   hipLaunchKernelGGL(pack_vt_kernel, dim3(nb, d.P * d.H_kv), dim3(256), 0, s, static_cast<const bf16_t*>(v),
                      d.n_tokens, nb, w.v_absmax, static_cast<uint16_t*>(w.vt));
