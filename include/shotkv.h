@@ -172,6 +172,10 @@ SHOTKV_API int shotkv_select_and_compact(const shotkv_config* cfg, int32_t P, in
  * Every other argument is as in shotkv_prefill_compress, and so is every result: shot_scores agree with
  * that entry point's to rounding.  Shapes: bf16, head_dim 128, per-layer head mode; anything else returns
  * SHOTKV_E_SHAPE.  The workspace (shotkv_prefill_attention_workspace_bytes) also holds a packed copy of V.
+ * Accuracy of attn_out: Q K^T in bf16 with fp32 accumulation, the weighted sum of V rows in fp16 (weights
+ * with 11 significant bits, V scaled per KV-head plane by an exact power of two so that any finite bf16
+ * values are representable) with fp32 accumulation and fp32 weight sums: each output row is within 1e-3 of
+ * its largest magnitude of the exact result.
  */
 SHOTKV_API size_t shotkv_prefill_attention_workspace_bytes(const shotkv_config* cfg, int32_t P, int32_t n_tokens,
                                                 int32_t n_shots);
