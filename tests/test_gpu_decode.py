@@ -43,7 +43,33 @@ def _make_state(kv, shape, st):
                           st["slot_pos"], st["decode_budget"], shape.n_q_heads, shape.sm_scale)
 
 
-def _compare_step(state, s, r, seq, near_ties):
+class PoolMirror:
+    """A device copy of the oracle's slot pool of one sequence, for the long lock-step test: every step the
+    row the oracle appended is uploaded and the device pool is compared with the copy on the device, whole
+    and bitwise; that the copy still equals the oracle's arrays is checked on the host every `every` steps
+    and by the caller at the end (check_against_oracle)."""
+
+    def __init__(self, state, seq, every=64):
+        self.k = torch.from_numpy(seq.kd).to(state.k_dec.dtype).cuda()
+        self.v = torch.from_numpy(seq.vd).to(state.v_dec.dtype).cuda()
+        self.every, self.n = every, 0
+
+    def check_against_oracle(self, seq):
+        np.testing.assert_array_equal(to_np(self.k), seq.kd)
+        np.testing.assert_array_equal(to_np(self.v), seq.vd)
+
+    def step(self, state, s, r, seq):
+        slot = r["new_slot"]
+        if slot >= 0:
+            self.k[:, slot] = torch.from_numpy(np.ascontiguousarray(seq.kd[:, slot])).to(self.k.dtype).cuda()
+            self.v[:, slot] = torch.from_numpy(np.ascontiguousarray(seq.vd[:, slot])).to(self.v.dtype).cuda()
+        assert torch.equal(state.k_dec[s], self.k) and torch.equal(state.v_dec[s], self.v)
+        self.n += 1
+        if self.n % self.every == 0:
+            self.check_against_oracle(seq)
+
+
+def _compare_step(state, s, r, seq, near_ties, mirror=None):
     """Device results of sequence s against the oracle's step result r."""
     assert int(state.status[s].item()) == r["status"]
     out = state.out[s].cpu().numpy().astype(np.float64)
@@ -64,8 +90,11 @@ def _compare_step(state, s, r, seq, near_ties):
         near_ties.append((s, ev))
     np.testing.assert_array_equal(state.slot_pos[s].cpu().numpy(), seq.slot_pos)
     # the slot pool itself: the appended K/V rows are bit-exact copies, nothing else is touched
-    np.testing.assert_array_equal(to_np(state.k_dec[s]), seq.kd)
-    np.testing.assert_array_equal(to_np(state.v_dec[s]), seq.vd)
+    if mirror is not None:
+        mirror.step(state, s, r, seq)
+    else:
+        np.testing.assert_array_equal(to_np(state.k_dec[s]), seq.kd)
+        np.testing.assert_array_equal(to_np(state.v_dec[s]), seq.vd)
 
 
 def test_tiny_free_running_320_steps(kv):
@@ -102,6 +131,7 @@ def test_decode4k_bf16_lockstep(kv, group):
     st = wl.decode_state(shape, "cuda", resident=resident)
     state = _make_state(kv, shape, st)
     tracked = {s: OracleSeq(st, s) for s in range(group, shape.n_seqs, 4)}
+    mirrors = {s: PoolMirror(state, seq) for s, seq in tracked.items()}
     vsum_before = st["v_prefill"].float().sum().item()
     near = []
     for step in range(resident, resident + steps):
@@ -110,9 +140,13 @@ def test_decode4k_bf16_lockstep(kv, group):
         torch.cuda.synchronize()
         for s, seq in tracked.items():
             r = seq.step(shape.decode_budget, step, q[s], kn[s], vn[s], shape.sm_scale)
-            _compare_step(state, s, r, seq, near)
+            _compare_step(state, s, r, seq, near, mirrors[s])
             assert (r["evicted_pos"] >= 0) == (step >= shape.decode_budget)
         assert state.status.cpu().tolist() == [0] * shape.n_seqs
+    for s, seq in tracked.items():
+        mirrors[s].check_against_oracle(seq)
+        np.testing.assert_array_equal(to_np(state.k_dec[s]), seq.kd)
+        np.testing.assert_array_equal(to_np(state.v_dec[s]), seq.vd)
     counts = (state.slot_pos >= 0).sum(dim=1).cpu().tolist()
     assert counts == [shape.decode_budget] * shape.n_seqs
     assert st["v_prefill"].float().sum().item() == vsum_before
