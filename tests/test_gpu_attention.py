@@ -131,6 +131,28 @@ def test_layer8k_fused(kv):
     assert not report, report
 
 
+def test_attn32k_fused(kv):
+    """The 32768-token problem bench.py times (one problem of the 32K workload's shape): sampled output rows
+    across the whole triangle, every score, the selection and the compacted cache against the oracle, and
+    the scores against the stand-alone entry point."""
+    import dataclasses
+    shape = dataclasses.replace(wl.PREFILL_SHAPES["model32k"], n_problems=1)
+    q, q_obs, k, v, off, bud = _problem_batch(shape, 0)
+    N, W = shape.n_tokens, shape.window
+    attn, res = kv.prefill_attention_compress(q, k, v, off, bud, shape.budget_tokens, W, shape.sm_scale)
+    torch.cuda.synchronize()
+    assert torch.isfinite(attn).all()
+    _check_rows(attn[0], q[0], k[0], v[0], [0, 31, 4095, 16384, 16511, 30000, N - W - 1, N - W, N - 1], shape.sm_scale)
+    report = []
+    check_prefill_problem(res, 0, q_obs[0], k[0], v[0], off[0].cpu().numpy(), shape.budget_tokens,
+                          shape.budget_tokens, shape.sm_scale, report=report)
+    assert not report, report
+    res2 = kv.prefill_compress(q_obs, k, v, off, bud, shape.budget_tokens, shape.sm_scale)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(res.shot_scores.cpu().numpy(), res2.shot_scores.cpu().numpy(), rtol=2e-5)
+    assert torch.equal(res.shot_selected, res2.shot_selected) and torch.equal(res.kept_count, res2.kept_count)
+
+
 def test_fused_entry_point_rejects_what_it_does_not_cover(kv):
     shape = wl.TINY            # fp32, head_dim 64
     q_obs, k, v, off, bud = wl.prefill_batch(shape, "cuda")
