@@ -170,7 +170,7 @@ SHOTKV_API int shotkv_select_and_compact(const shotkv_config* cfg, int32_t P, in
  *   q   [P][H][n_tokens][D] dtype   all query rows of the layer (the last W are the window queries)
  *
  * Every other argument is as in shotkv_prefill_compress, and so is every result: shot_scores agree with
- * that entry point's to rounding.  Shapes: bf16, head_dim 128, per-layer head mode; anything else returns
+ * that entry point's to rounding (both head modes).  Shapes: bf16, head_dim 128; anything else returns
  * SHOTKV_E_SHAPE.  The workspace (shotkv_prefill_attention_workspace_bytes) also holds a packed copy of V.
  * Accuracy of attn_out: Q K^T in bf16 with fp32 accumulation, the weighted sum of V rows in fp16 (weights
  * with 11 significant bits, V scaled per KV-head plane by an exact power of two so that any finite bf16

@@ -209,7 +209,6 @@ int shotkv_prefill_compress(const shotkv_config* cfg, int32_t P, int32_t n_token
 static int make_attention_dims(const shotkv_config* cfg, int P, int n_tokens, int n_shots, PrefillDims* d) {
   const int rc = make_prefill_dims(cfg, P, n_tokens, n_shots, d);
   if (rc != SHOTKV_OK) return rc;
-  if (cfg->head_mode != SHOTKV_HEADS_PER_LAYER) return SHOTKV_E_SHAPE;
   if (!attention_supported(*d)) return SHOTKV_E_SHAPE;
   d->R = d->R_rows;
   return SHOTKV_OK;

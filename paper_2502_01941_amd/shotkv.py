@@ -241,16 +241,17 @@ def prefill_compress(q_obs, k, v, shot_offsets, budget_tokens, cap, sm_scale,
 
 def prefill_attention_compress(q, k, v, shot_offsets, budget_tokens, cap, window, sm_scale,
                                select_mode=SELECT_PREFIX, out: PrefillResult | None = None, workspace=None,
-                               attn_out=None):
+                               attn_out=None, head_mode=HEADS_PER_LAYER):
     """shotkv_prefill_attention_compress.  q [P,H,N,D] (all query rows), k/v [P,H_kv,N,D], window = W.
     Returns (attn_out [P,H,N,D] float32, PrefillResult); nothing is synchronised."""
     P, H, N, D = q.shape
     _, H_kv, _, _ = k.shape
     n = shot_offsets.shape[1] - 1
-    cfg = _config(H, H_kv, D, window, k.dtype, sm_scale, select_mode, HEADS_PER_LAYER)
+    cfg = _config(H, H_kv, D, window, k.dtype, sm_scale, select_mode, head_mode)
     lib = load_library()
+    lead = (P,) + _per(head_mode, H_kv)
     if out is None:
-        out = _alloc_prefill_outputs(k, P, H_kv, cap, D, n)
+        out = _alloc_prefill_outputs(k, P, H_kv, cap, D, n, head_mode=head_mode)
     if attn_out is None:
         attn_out = torch.empty((P, H, N, D), dtype=torch.float32, device=k.device)
     if workspace is None:
@@ -264,10 +265,10 @@ def prefill_attention_compress(q, k, v, shot_offsets, budget_tokens, cap, window
         _ptr(budget_tokens, torch.int32, (P,), "budget_tokens"),
         _ptr(attn_out, torch.float32, (P, H, N, D), "attn_out"),
         _ptr(out.k_out, k.dtype, (P, H_kv, cap, D), "k_out"), _ptr(out.v_out, k.dtype, (P, H_kv, cap, D), "v_out"),
-        cap, _ptr(out.kept_positions, torch.int32, (P, cap), "kept_positions"),
-        _ptr(out.kept_count, torch.int32, (P,), "kept_count"),
-        _ptr(out.shot_scores, torch.float32, (P, n), "shot_scores"),
-        _ptr(out.shot_selected, torch.uint8, (P, n), "shot_selected"), _ptr(out.status, torch.int32, (P,), "status"),
+        cap, _ptr(out.kept_positions, torch.int32, lead + (cap,), "kept_positions"),
+        _ptr(out.kept_count, torch.int32, lead, "kept_count"),
+        _ptr(out.shot_scores, torch.float32, lead + (n,), "shot_scores"),
+        _ptr(out.shot_selected, torch.uint8, lead + (n,), "shot_selected"), _ptr(out.status, torch.int32, lead, "status"),
         _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
     _check(rc, "shotkv_prefill_attention_compress")
     return attn_out, out

@@ -153,6 +153,39 @@ def test_attn32k_fused(kv):
     assert torch.equal(res.shot_selected, res2.shot_selected) and torch.equal(res.kept_count, res2.kept_count)
 
 
+def test_fused_per_kv_head(kv):
+    """The per-KV-head variant through the fused entry point: the attention output is the same (it does not
+    depend on the head mode), every KV head selects over its own query group exactly as the stand-alone
+    entry point does, and the result matches the oracle's per-KV-head compression."""
+    import types
+    H, H_kv, W, N, n_shots, P = 8, 4, 16, 1100, 7, 2
+    budget, G = N // 2, 2
+    shape = wl.PrefillShape("attn", P, H, H_kv, 128, W, N, n_shots, torch.bfloat16, budget, len_lo=90, len_hi=140)
+    q, q_obs, k, v, off, bud = _problem_batch(shape, 41)
+    attn, res = kv.prefill_attention_compress(q, k, v, off, bud, budget, W, shape.sm_scale,
+                                              head_mode=kv.HEADS_PER_KV_HEAD)
+    attn_layer, _ = kv.prefill_attention_compress(q, k, v, off, bud, budget, W, shape.sm_scale)
+    res2 = kv.prefill_compress(q_obs, k, v, off, bud, budget, shape.sm_scale, head_mode=kv.HEADS_PER_KV_HEAD)
+    torch.cuda.synchronize()
+    assert torch.equal(attn, attn_layer)
+    assert res.kept_count.shape == (P, H_kv) and res.kept_positions.shape == (P, H_kv, budget)
+    np.testing.assert_allclose(res.shot_scores.cpu().numpy(), res2.shot_scores.cpu().numpy(), rtol=2e-5)
+    assert torch.equal(res.shot_selected, res2.shot_selected) and torch.equal(res.kept_count, res2.kept_count)
+    view = types.SimpleNamespace(
+        status=res.status.reshape(-1), kept_count=res.kept_count.reshape(-1),
+        shot_scores=res.shot_scores.reshape(P * H_kv, n_shots), shot_selected=res.shot_selected.reshape(P * H_kv, n_shots),
+        kept_positions=res.kept_positions.reshape(P * H_kv, budget),
+        k_out=res.k_out.reshape(P * H_kv, 1, budget, 128), v_out=res.v_out.reshape(P * H_kv, 1, budget, 128))
+    for p in range(P):
+        refs = orc.prefill_compress_per_kv_head(to_np(q_obs[p]), to_np(k[p]), to_np(v[p]), off[p].cpu().numpy(),
+                                                budget, shape.sm_scale, orc.SELECT_PREFIX)
+        for g in range(H_kv):
+            check_prefill_problem(view, p * H_kv + g, q_obs[p, g * G:(g + 1) * G], k[p, g:g + 1], v[p, g:g + 1],
+                                  off[p].cpu().numpy(), budget, budget, shape.sm_scale, orc.SELECT_PREFIX,
+                                  ref=refs[g])
+    _check_rows(attn[0], q[0], k[0], v[0], [0, 63, 500, N - 1], shape.sm_scale)
+
+
 def test_fused_entry_point_rejects_what_it_does_not_cover(kv):
     shape = wl.TINY            # fp32, head_dim 64
     q_obs, k, v, off, bud = wl.prefill_batch(shape, "cuda")
