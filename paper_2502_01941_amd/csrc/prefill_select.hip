@@ -4,8 +4,8 @@
 //
 //   scores    Score(s_i) = (sum of the masses of the shot's chunks) / k_i;
 //   ranking   bitonic sort on one 64-bit key per shot (score descending, shot index ascending): keys
-//             live in registers, partners less than 64 apart are exchanged with lane shuffles, and
-//             for the larger strides the keys pass through LDS into a transposed layout in which
+//             live in registers, partners less than 64 apart are exchanged between lanes without LDS
+//             (DPP moves inside a row of 16, row and half swaps beyond), and for the larger strides the keys pass through LDS into a transposed layout in which
 //             those strides are lane distances too - two LDS round trips per merge level instead of
 //             one per compare-exchange step;
 //   budget    prefix sum of shot lengths in rank order (or the sequential first-fit walk);
