@@ -147,7 +147,8 @@ SHOTKV_API int shotkv_prefill_scores(const shotkv_config* cfg, int32_t P, int32_
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /* The selection and compaction half alone (steps 3-4 above; Eq. 4-6) from caller-supplied scores.
- * Arguments as in shotkv_prefill_compress; shot_scores is an input here. */
+ * Arguments as in shotkv_prefill_compress; shot_scores is an input here.  -0 ranks with +0; a NaN has no
+ * rank and is placed by its bit pattern (deterministic, otherwise unspecified). */
 SHOTKV_API int shotkv_select_and_compact(const shotkv_config* cfg, int32_t P, int32_t n_tokens, int32_t n_shots,
                               const float* shot_scores, const void* k, const void* v,
                               const int32_t* shot_offsets, const int32_t* budget_tokens,
