@@ -149,7 +149,7 @@ def main():
                     help="also run a plain 1 GiB device copy (known traffic) for scaling profiler byte counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py measures one GPU's throughput; this build has no multi-GPU path (run with --gpus 1)",
+        print("bench.py measures one GPU's throughput; the library has no multi-GPU path (run with --gpus 1)",
               file=sys.stderr)
         sys.exit(2)
 
