@@ -30,7 +30,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `rocprofv3 --pmc` runs of this file, see profiles/score_partials_mfma_model32k_counters.md).  Valid only
 # for the kernel source it was measured on: reported as null once that file's hash differs.
 SCORE_KERNEL_SOURCE = os.path.join(ROOT, "paper_2502_01941_amd", "csrc", "prefill_score_mfma.hip")
-MEASURED_TRAFFIC = {"model32k": {"sha256": "c47e800866cfa26fb957fa8ce8a91203711c352e8e642ef93be0735bcda9146e",
+MEASURED_TRAFFIC = {"model32k": {"sha256": "864e57a17e23b5707280de8a5e16578af9d20837ac6324b9182bbe9136777c50",
                                  "bytes": 8.96e9}}
 
 PREFILL_KINDS = ("plan", "score", "row_stats", "chunk_mass", "reduce_select", "compact")

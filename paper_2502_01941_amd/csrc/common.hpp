@@ -119,14 +119,14 @@ struct PrefillWorkspace {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-int score_group_keys(int P, int H_kv, int n_tokens);  // keys per workgroup of the matrix-core score kernel
+int score_group_keys(int P, int H_kv, int n_tokens, int n_shots);  // keys per workgroup of the matrix-core score kernel
 
 inline PrefillWorkspace carve_prefill(void* base, int P, int H_kv, int R, int n_tokens, int n_shots,
                                       bool mfma_score, size_t vt_bytes = 0) {
   PrefillWorkspace w{};
   w.chunk_keys = mfma_score ? kChunkKeys : kChunkKeysGeneric;
   w.max_c = max_chunks(n_tokens, n_shots, w.chunk_keys);
-  w.group_keys = mfma_score ? score_group_keys(P, H_kv, n_tokens) : 0;
+  w.group_keys = mfma_score ? score_group_keys(P, H_kv, n_tokens, n_shots) : 0;
   w.n_groups = mfma_score ? ceil_div(n_tokens, w.group_keys) : w.max_c;
   size_t off = 0;
   char* b = static_cast<char*>(base);

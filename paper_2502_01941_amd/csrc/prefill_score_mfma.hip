@@ -540,17 +540,22 @@ score_partials_mfma_kernel(
 
 }  // namespace
 
-int score_group_keys(int P, int H_kv, int n_tokens) {
+int score_group_keys(int P, int H_kv, int n_tokens, int n_shots) {
 #ifdef SHOTKV_SCORE_GROUP_KEYS
   return SHOTKV_SCORE_GROUP_KEYS;
 #else
-  // a workgroup takes the chunks that start inside a slice of the key axis: slices long enough to
-  // amortise its query registers, short enough that 256 CUs x 6 resident pairs are kept busy several
-  // times over (about 16K workgroups for a large batch)
+  // A workgroup takes the chunks that start inside a slice of the key axis.  Long slices amortise its
+  // query registers and its start-up, but the chip wants a thousand workgroups or more: measured on
+  // batches of 1 to 128 problems of 32K tokens, 2048-key slices win from about four thousand workgroups
+  // on, 1024-key slices from about one thousand on, and below that the count matters more than the length.
   const long total_keys = static_cast<long>(n_tokens) * H_kv * P;
-  long keys = (total_keys / 16384L + 255) / 256 * 256;
-  if (keys < 256) keys = 256;  // a single layer of a few thousand tokens: more, shorter workgroups
-  if (keys > 2048) keys = 2048;
+  long keys = 256;
+  if (total_keys >= 2048L * 4096L) keys = 2048;
+  else if (total_keys >= 1024L * 1024L) keys = 1024;
+  else if (total_keys >= 512L * 1024L) keys = 512;
+  // sentence-sized units: most blocks hold a boundary and cost twice a plain block, so the workgroups'
+  // run times differ more and shorter ones balance better (3 % at 1240 units per 32K tokens)
+  if (n_shots > 0 && n_tokens / n_shots < 64 && keys > 512) keys = 512;
   return static_cast<int>(keys);
 #endif
 }
