@@ -276,6 +276,23 @@ def test_maximum_number_of_shots_end_to_end(kv):
         kv.prefill_scores(q, k, torch.zeros((1, n + 2), dtype=torch.int32, device="cuda"), 0.1)
 
 
+def test_one_million_tokens(kv):
+    """A context of 2^20 + 37 tokens with the largest number of shots (lengths 1 to ~2500): row offsets past
+    2^28 bytes inside a plane, a thousand score workgroups per KV head, eight thousand chunks, a copy plan of
+    350 K positions."""
+    P, H, Hkv, D, W, n = 1, 4, 1, 128, 32, 4096
+    N = (1 << 20) + 37
+    q, k, v, off = _ragged_problem(P, H, Hkv, D, W, N, torch.bfloat16, 991, n, prefix=3, tail_min=W + 500)
+    budget = N // 3
+    bud = torch.tensor([budget], dtype=torch.int32, device="cuda")
+    scale = 1.0 / math.sqrt(D)
+    res = kv.prefill_compress(q, k, v, off, bud, budget, scale)
+    torch.cuda.synchronize()
+    report = []
+    check_prefill_problem(res, 0, q[0], k[0], v[0], off[0].cpu().numpy(), budget, budget, scale, report=report)
+    print("near ties:", report)
+
+
 @pytest.mark.parametrize("H,Hkv", [(8, 2), (4, 2), (2, 2), (12, 2), (16, 2)])
 def test_units_of_one_to_three_tokens(kv, H, Hkv):
     """Units of one to three tokens: up to thirty-two chunk boundaries inside one 32-key block, at every
