@@ -16,6 +16,7 @@ import argparse
 import hashlib
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -203,15 +204,16 @@ def main():
     # ---- kernel durations: a separate pass of the same step, each kernel between caller-owned events
     timers = shotkv.KernelTimers()
     kinds = PREFILL_KINDS + ("decode_partial", "decode_finish")
-    sums = {x: 0.0 for x in kinds}
+    seen = {x: [] for x in kinds}
     with timers:
         for i in range(args.kernel_warmup + args.kernel_steps):
             step(steps_done + i)
             for x, ms in timers.read(kinds).items():
                 if i >= args.kernel_warmup:
-                    sums[x] += ms
+                    seen[x].append(ms)
     steps_done += args.kernel_warmup + args.kernel_steps
-    kernels = {x: {"avg_ms": sums[x] / args.kernel_steps, "launches": args.kernel_steps} for x in kinds}
+    kernels = {x: {"avg_ms": sum(seen[x]) / args.kernel_steps, "median_ms": statistics.median(seen[x]),
+                   "min_ms": min(seen[x]), "launches": args.kernel_steps} for x in kinds}
     prefill_ms = _timed(torch, prefill, args.steps, 2)          # prefill compression alone, uninstrumented
 
     score_bytes = P * N * kvb                                   # K read once per launch
