@@ -16,6 +16,7 @@ pytestmark = pytest.mark.gpu
 N_SLICES = 8
 NEAR_TIES = {}      # workload name -> [(problem, margin, device agrees with the oracle end to end)]
 CHECKED = {}        # workload name -> set of problems the oracle has been run on
+ORACLE_SCORES = {}  # workload name -> {problem: the oracle's shot scores (float64)}
 
 
 @pytest.fixture(scope="module")
@@ -36,6 +37,7 @@ def full(request, kv):
     torch.cuda.synchronize()
     NEAR_TIES[shape.name] = []
     CHECKED[shape.name] = set()
+    ORACLE_SCORES[shape.name] = {}
     yield {"shape": shape, "q": q, "k": k, "v": v, "off": off, "bud": bud, "res": res}
     del q, k, v, res
     torch.cuda.empty_cache()
@@ -71,9 +73,10 @@ def test_oracle_on_every_problem(full, part):
     """Problems part, part + 8, ... of the workload against the oracle, element by element."""
     shape, q, k, v, off, res = full["shape"], full["q"], full["k"], full["v"], full["off"], full["res"]
     for p in range(part, shape.n_problems, N_SLICES):
-        check_prefill_problem(res, p, q[p], k[p], v[p], off[p].cpu().numpy(), shape.budget_tokens,
-                              shape.budget_tokens, shape.sm_scale, report=NEAR_TIES[shape.name])
+        ref = check_prefill_problem(res, p, q[p], k[p], v[p], off[p].cpu().numpy(), shape.budget_tokens,
+                                    shape.budget_tokens, shape.sm_scale, report=NEAR_TIES[shape.name])
         CHECKED[shape.name].add(p)
+        ORACLE_SCORES[shape.name][p] = ref["scores"]
 
 
 def test_near_tie_report(full, record_property):
@@ -91,6 +94,99 @@ def test_near_tie_report(full, record_property):
         scores = full["res"].shot_scores.cpu().numpy()
         for p in range(shape.n_problems):
             assert scores[p][sel[p] == 1].min() > 1.2 * np.median(scores[p])
+
+
+def _gather_is_exact(k, v, k_out, v_out, positions, kept):
+    idx = positions[:kept].long()
+    return torch.equal(k_out[:, :kept], k[:, idx]) and torch.equal(v_out[:, :kept], v[:, idx])
+
+
+def test_first_fit_on_every_problem(kv, full):
+    """The other selection rule at full size: same scores bit for bit (the score kernels do not know the
+    rule), the first-fit walk replayed on the device's own scores on every problem, the gather, and the
+    oracle's first-fit walk on the oracle's scores wherever its decision margin is at least 1e-6."""
+    from oracle import shotkv_oracle as orc
+    shape, q, k, v, off, bud, res = (full[x] for x in ("shape", "q", "k", "v", "off", "bud", "res"))
+    if shape.name == "skew128k":
+        pytest.skip("a handful of long shots: first fit and prefix keep the same shots")
+    assert len(ORACLE_SCORES[shape.name]) == shape.n_problems
+    P, N, cap = shape.n_problems, shape.n_tokens, shape.budget_tokens
+    ff = kv.prefill_compress(q, k, v, off, bud, cap, shape.sm_scale, select_mode=orc.SELECT_FIRST_FIT)
+    torch.cuda.synchronize()
+    assert ff.status.cpu().tolist() == [0] * P
+    assert torch.equal(ff.shot_scores, res.shot_scores)
+    offs, sel = off.cpu().numpy(), ff.shot_selected.cpu().numpy()
+    kept, pos_all, scores32 = ff.kept_count.cpu().numpy(), ff.kept_positions.cpu().numpy(), ff.shot_scores.cpu().numpy()
+    near, differs_from_prefix = [], 0
+    prefix_sel = res.shot_selected.cpu().numpy()
+    for p in range(P):
+        helpers.check_selection_valid(sel[p], int(kept[p]), pos_all[p, : kept[p]], offs[p], N, cap)
+        keep_replay, pos_replay = helpers.replay_selection(scores32[p], offs[p], N, cap, orc.SELECT_FIRST_FIT)
+        assert sel[p].tolist() == keep_replay.tolist(), p
+        np.testing.assert_array_equal(pos_all[p, : kept[p]], pos_replay)
+        assert _gather_is_exact(k[p], v[p], ff.k_out[p], ff.v_out[p], ff.kept_positions[p], int(kept[p])), p
+        lengths = np.diff(offs[p].astype(np.int64))
+        shot_budget = cap - int(offs[p][0]) - int(N - offs[p][-1])
+        ref_scores = ORACLE_SCORES[shape.name][p]
+        margin = orc.decision_margin(ref_scores, lengths, shot_budget, orc.SELECT_FIRST_FIT)
+        keep_ref = orc.select_shots(ref_scores, lengths, shot_budget, orc.SELECT_FIRST_FIT)
+        if margin >= helpers.MARGIN_EXACT:
+            assert sel[p].tolist() == keep_ref.tolist(), (p, margin)
+        else:
+            near.append((p, margin, sel[p].tolist() == keep_ref.tolist()))
+        assert kept[p] >= res.kept_count[p].item()       # first fit keeps the prefix rule's shots and more
+        differs_from_prefix += int(sel[p].tolist() != prefix_sel[p].tolist())
+    print(f"\n[{shape.name}] first fit: margin < {helpers.MARGIN_EXACT:g} on {len(near)}: {near}; "
+          f"differs from the prefix rule on {differs_from_prefix} of {P} problems")
+    assert len(near) <= max(2, P // 8), near
+    assert differs_from_prefix > 0
+
+
+def test_per_kv_head_on_every_problem(kv, full):
+    """The per-KV-head mode at full size (32K workload): per-head scores add up to the per-layer scores
+    (Eq. 3 is a sum over heads), every (problem, head) selection is the walk on its own scores and its
+    gather is exact, and every 8th problem goes through the per-head oracle element by element."""
+    from oracle import shotkv_oracle as orc
+    from helpers import to_np
+    shape, q, k, v, off, bud, res = (full[x] for x in ("shape", "q", "k", "v", "off", "bud", "res"))
+    if shape.name != "model32k":
+        pytest.skip("run on the 32K workload")
+    P, N, cap, n = shape.n_problems, shape.n_tokens, shape.budget_tokens, shape.n_shots
+    H, H_kv, D = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    G = H // H_kv
+    ph = kv.prefill_compress(q, k, v, off, bud, cap, shape.sm_scale, head_mode=kv.HEADS_PER_KV_HEAD)
+    torch.cuda.synchronize()
+    assert ph.status.cpu().tolist() == [[0] * H_kv] * P
+    torch.testing.assert_close(ph.shot_scores.double().sum(dim=1), res.shot_scores.double(), rtol=2e-5, atol=0)
+    offs, sel = off.cpu().numpy(), ph.shot_selected.cpu().numpy()
+    kept, pos_all, scores32 = ph.kept_count.cpu().numpy(), ph.kept_positions.cpu().numpy(), ph.shot_scores.cpu().numpy()
+    distinct = set()
+    for p in range(P):
+        for g in range(H_kv):
+            c = int(kept[p, g])
+            helpers.check_selection_valid(sel[p, g], c, pos_all[p, g, :c], offs[p], N, cap)
+            keep_replay, pos_replay = helpers.replay_selection(scores32[p, g], offs[p], N, cap, orc.SELECT_PREFIX)
+            assert sel[p, g].tolist() == keep_replay.tolist(), (p, g)
+            np.testing.assert_array_equal(pos_all[p, g, :c], pos_replay)
+            assert _gather_is_exact(k[p, g:g + 1], v[p, g:g + 1], ph.k_out[p, g:g + 1], ph.v_out[p, g:g + 1],
+                                    ph.kept_positions[p, g], c), (p, g)
+        distinct.add(tuple(sel[p].reshape(-1).tolist()))
+    assert len(distinct) == P
+    import types
+    view = types.SimpleNamespace(
+        status=ph.status.reshape(-1), kept_count=ph.kept_count.reshape(-1),
+        shot_scores=ph.shot_scores.reshape(P * H_kv, n), shot_selected=ph.shot_selected.reshape(P * H_kv, n),
+        kept_positions=ph.kept_positions.reshape(P * H_kv, cap),
+        k_out=ph.k_out.reshape(P * H_kv, 1, cap, D), v_out=ph.v_out.reshape(P * H_kv, 1, cap, D))
+    near = []
+    for p in range(0, P, 8):
+        o = off[p].cpu().numpy()
+        refs = orc.prefill_compress_per_kv_head(to_np(q[p]), to_np(k[p]), to_np(v[p]), o, cap, shape.sm_scale)
+        for g in range(H_kv):
+            check_prefill_problem(view, p * H_kv + g, q[p, g * G:(g + 1) * G], k[p, g:g + 1], v[p, g:g + 1], o,
+                                  cap, cap, shape.sm_scale, report=near, ref=refs[g])
+    print(f"\n[{shape.name}] per KV head: margin < {helpers.MARGIN_EXACT:g} on {len(near)} of {P // 8 * H_kv}: {near}")
+    assert len(near) <= 4, near
 
 
 def test_decode_over_the_compressed_caches(kv, full):
