@@ -126,3 +126,49 @@ def test_decode_per_kv_head_lockstep(kv, dtype, D, H, H_kv):
             evicted.add(tuple(state.evicted_pos.view(-1).cpu().tolist()))
     assert len(near) == 0, near
     assert any(len(set(e)) > 1 for e in evicted)      # heads do evict different tokens
+
+
+def test_decode4k_per_kv_head_lockstep(kv):
+    """The long-generation shape in the per-KV-head mode: 16 sequences x 8 KV heads, each (sequence, head)
+    with its own live row count (3000..4096) and its own slot map, 1020 resident tokens and 12 steps, so
+    that every pair starts evicting on the fifth.  Every pair is followed by the oracle as a sequence of its
+    own with G = 4 query heads."""
+    shape = wl.DECODE4K
+    S, H, H_kv, D, cap, budget = (shape.n_seqs, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                                  shape.prefill_count, shape.decode_budget)
+    G, n_slots, resident, steps = H // H_kv, budget + 1, budget - 4, 12
+    st = wl.decode_state(shape, "cuda", 21, resident=resident)
+    gen = torch.Generator().manual_seed(5)
+    pc = torch.randint(3000, cap + 1, (S, H_kv), generator=gen, dtype=torch.int32).cuda()
+    slot_pos = st["slot_pos"][:, None, :].expand(S, H_kv, n_slots).contiguous()
+    state = kv.DecodeState(st["k_prefill"], st["v_prefill"], pc, st["k_dec"], st["v_dec"], slot_pos, budget,
+                           H, shape.sm_scale, head_mode=kv.HEADS_PER_KV_HEAD)
+    seqs = {}
+    for s in range(S):
+        for g in range(H_kv):
+            one = {"k_prefill": st["k_prefill"][:, g:g + 1], "v_prefill": st["v_prefill"][:, g:g + 1],
+                   "prefill_count": pc[:, g], "k_dec": st["k_dec"][:, g:g + 1], "v_dec": st["v_dec"][:, g:g + 1],
+                   "slot_pos": slot_pos[:, g]}
+            seq = OracleSeq(one, s)
+            seq.kp, seq.vp = seq.kp[:, :seq.pc].copy(), seq.vp[:, :seq.pc].copy()
+            seqs[(s, g)] = seq
+    view = types.SimpleNamespace(status=state.status.view(-1), out=state.out.view(S * H_kv, G, D),
+                                 token_scores=state.token_scores.view(S * H_kv, n_slots),
+                                 evicted_pos=state.evicted_pos.view(-1), slot_pos=slot_pos.view(S * H_kv, n_slots),
+                                 k_dec=st["k_dec"].view(S * H_kv, 1, n_slots, D),
+                                 v_dec=st["v_dec"].view(S * H_kv, 1, n_slots, D))
+    near, evicted = [], set()
+    for step in range(resident, resident + steps):
+        q, kn, vn = wl.decode_inputs(shape, step, "cuda", 21)
+        kv.decode_step(state, step, q, kn, vn)
+        torch.cuda.synchronize()
+        for (s, g), seq in seqs.items():
+            r = seq.step(budget, step, q[s, g * G:(g + 1) * G], kn[s, g:g + 1], vn[s, g:g + 1], shape.sm_scale)
+            _compare_step(view, s * H_kv + g, r, seq, near)
+            assert (r["evicted_pos"] >= 0) == (step >= budget)
+        if step >= budget:
+            evicted.add(tuple(state.evicted_pos.view(-1).cpu().tolist()))
+    print(f"\n[decode4k per KV head] near-tie evictions followed: {near}")
+    assert len(near) <= 2, near
+    assert all(len(set(e)) > 1 for e in evicted)      # heads evict different tokens
+    assert ((slot_pos >= 0).sum(dim=2) == budget).all()
