@@ -51,6 +51,28 @@ def test_eviction_tie_goes_to_newest_and_new_token_is_exempt():
     assert r["margin"] == 0.0
 
 
+def test_softmax_over_the_union_is_shift_invariant_at_large_logits():
+    """Prefill key with logit 1000, decode keys with 1000 + ln 2 and (the new token) 1000 + ln 3: weights
+    1/6, 2/6, 3/6, which a plain exp(1000) could not produce."""
+    kp = np.array([[[0.0, 1.0]]]); vp = np.array([[[6.0, 0.0]]])
+    kd = np.array([[[math.log(2.0), 1.0], [0.0, 0.0]]]); vd = np.array([[[12.0, 0.0], [0.0, 0.0]]])
+    slot_pos = np.array([0, -1], dtype=np.int32)
+    r = orc.decode_step(kp, vp, 1, kd, vd, slot_pos, 5, 1, np.array([[1.0, 1000.0]]),
+                        np.array([[math.log(3.0), 1.0]]), np.array([[18.0, 0.0]]), 1.0)
+    np.testing.assert_allclose(r["token_scores"], [2 / 6, 3 / 6], rtol=1e-12)
+    np.testing.assert_allclose(r["out"][0], [(6 + 2 * 12 + 3 * 18) / 6, 0.0], rtol=1e-12)
+
+
+def test_eviction_margin_leaves_out_the_new_token_and_free_slots():
+    scores = np.array([0.5, 0.1, 0.4, 0.3, 0.0])
+    slot_pos = np.array([4, 9, 2, 7, -1])
+    # candidates 0.5, 0.4, 0.3 (slot 1 holds the new token, slot 4 is free): (0.4 - 0.3) / 0.4
+    assert abs(orc.eviction_margin(scores, slot_pos, 1) - 0.25) < 1e-12
+    # with slot 0 as the new token the candidates are 0.1, 0.4, 0.3: (0.3 - 0.1) / 0.3
+    assert abs(orc.eviction_margin(scores, slot_pos, 0) - 2.0 / 3.0) < 1e-12
+    assert orc.eviction_margin(scores, np.array([4, 9, -1, -1, -1]), 1) == np.inf
+
+
 def test_output_matches_library_attention_and_scores_sum_to_heads():
     rng = np.random.default_rng(4)
     H, Hkv, D, cap, pc, n_slots = 6, 2, 8, 12, 9, 7

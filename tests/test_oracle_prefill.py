@@ -250,6 +250,55 @@ def test_degenerate_inputs():
     assert r["status"] == orc.STATUS_OK and r["kept_positions"].tolist() == list(range(6, 12))
 
 
+def test_boundary_cases_of_the_offset_check_and_a_window_as_long_as_the_prompt():
+    """The last shot may end at the last token, and the window may be the whole prompt (then every query
+    row is causally masked); one past either is an error."""
+    assert orc.offsets_valid([0, 4, 8], 8, 2) and not orc.offsets_valid([0, 4, 9], 8, 2)
+    assert orc.offsets_valid([0, 1], 4, 4) and not orc.offsets_valid([0, 1], 4, 5)
+    # W = N = 3, keys all equal: query j sees keys 0..j with weight 1/(j+1), so over H heads
+    # mass = H * (1 + 1/2 + 1/3, 1/2 + 1/3, 1/3); the one shot [0, 3) has score H * 3 / 3
+    H = 2
+    q = np.ones((H, 3, 2)); k = np.zeros((1, 3, 2)); v = np.arange(6.0).reshape(1, 3, 2)
+    r = orc.prefill_compress(q, k, v, [0, 3], 3, 1.0)
+    assert r["status"] == orc.STATUS_OK and r["kept_positions"].tolist() == [0, 1, 2]
+    np.testing.assert_allclose(r["mass"], [float(H * Fraction(11, 6)), float(H * Fraction(5, 6)), float(H * Fraction(1, 3))],
+                               rtol=1e-14)
+    np.testing.assert_allclose(r["scores"], [float(H)], rtol=1e-14)
+    assert orc.prefill_compress(q, k, v, [0, 4], 3, 1.0)["status"] == orc.STATUS_BAD_OFFSETS
+
+
+def test_softmax_is_shift_invariant_at_logits_that_overflow_a_plain_exponential():
+    """Logits x_t + 1000 with x = (0, ln 2, ln 3): the weights are 1/6, 2/6, 3/6 whatever the common offset
+    (exp(1000) is not representable, so this only holds when the maximum is taken out first)."""
+    k = np.array([[[0.0, 1.0], [math.log(2.0), 1.0], [math.log(3.0), 1.0]]])      # [1, 3, 2]
+    q = np.array([[[1.0, 1000.0]]])                                                # [1, 1, 2]: W = 1 sees all keys
+    p = orc.window_attention(q, k, 1.0)
+    np.testing.assert_allclose(p[0, 0], [1 / 6, 2 / 6, 3 / 6], rtol=1e-12)
+    v = np.array([[[6.0, 0.0], [12.0, 0.0], [18.0, 0.0]]])
+    qs = np.repeat(q, 3, axis=1)                                                   # the same query at every position
+    out = orc.causal_attention(qs, k, v, 1.0)
+    np.testing.assert_allclose(out[0, :, 0], [6.0, (6 + 2 * 12) / 3, (6 + 2 * 12 + 3 * 18) / 6], rtol=1e-12)
+
+
+def test_scores_given_from_outside_decide_the_selection():
+    """The walk can be replayed on scores that come from elsewhere (a device's): they rank the shots and
+    set the margin, while the result still reports the scores computed here."""
+    rng = np.random.default_rng(31)
+    q, k, v = _rand_problem(rng, 2, 1, 4, 2, 20)
+    off = [0, 6, 12, 18]
+    own = orc.prefill_compress(q, k, v, off, 8, 1.0)              # room for one shot
+    best = int(np.argmax(own["scores"]))
+    assert own["selected"].tolist() == [int(i == best) for i in range(3)]
+    other = (best + 1) % 3
+    given = np.array([1.0, 1.0, 1.0]); given[other] = 2.0; given[best] = 0.5
+    r = orc.prefill_compress(q, k, v, off, 8, 1.0, scores_override=given)
+    assert r["selected"].tolist() == [int(i == other) for i in range(3)]
+    np.testing.assert_array_equal(r["scores"], own["scores"])
+    assert r["kept_positions"].tolist() == list(range(6 * other, 6 * other + 6)) + [18, 19]
+    assert abs(r["margin"] - 0.5) < 1e-12                          # (2 - 1) / 2, from the given scores
+    np.testing.assert_array_equal(r["k_out"], k[:, r["kept_positions"]])
+
+
 def test_workload_layouts():
     for shape in wl.PREFILL_SHAPES.values():
         for p in (0, 1):
