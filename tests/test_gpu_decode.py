@@ -179,20 +179,32 @@ def test_partial_prefill_and_unbounded_budget(kv):
                 np.testing.assert_array_equal(state.slot_pos[s].cpu().numpy(), seqs[s].slot_pos)
 
 
-def test_equal_scores_evict_newest_previous_token(kv):
+@pytest.mark.parametrize("H,H_kv,D,dtype", [(4, 4, 64, torch.float32), (8, 2, 128, torch.bfloat16)])
+def test_equal_scores_evict_newest_previous_token(kv, H, H_kv, D, dtype):
     """All decode keys identical -> equal token scores; the evicted token must be the newest earlier
-    one, never the token just appended."""
-    shape = wl.DecodeShape("ties", 1, 4, 4, 64, 8, 3, 0, torch.float32)
+    one, never the token just appended: checked against the hand-written sequence and, strictly (a tie is
+    no excuse here), against the oracle at every step."""
+    shape = wl.DecodeShape("ties", 1, H, H_kv, D, 8, 3, 0, dtype)
     st = wl.decode_state(shape, "cuda")
     state = _make_state(kv, shape, st)
-    q = torch.ones((1, 4, 64), device="cuda")
-    kn = torch.full((1, 4, 64), 0.25, device="cuda")
-    vn = torch.ones((1, 4, 64), device="cuda")
+    seq = OracleSeq(st, 0)
+    q = torch.ones((1, H, D), device="cuda").to(dtype)
+    kn = torch.full((1, H_kv, D), 0.25, device="cuda").to(dtype)
+    vn = torch.ones((1, H_kv, D), device="cuda").to(dtype)
     evicted = []
     for step in range(6):
         kv.decode_step(state, step, q, kn, vn)
         torch.cuda.synchronize()
         evicted.append(int(state.evicted_pos[0].item()))
+        r = seq.step(shape.decode_budget, step, q[0], kn[0], vn[0], shape.sm_scale)
+        assert evicted[-1] == r["evicted_pos"] and (step < 3 or r["margin"] == 0.0)
+        np.testing.assert_array_equal(state.slot_pos[0].cpu().numpy(), seq.slot_pos)
+        if step >= 1:       # the decode tokens' scores are equal to the last bit on the device as well
+            ts = state.token_scores[0].cpu().numpy()
+            held = ts[seq.slot_pos >= 0].tolist()
+            if r["evicted_slot"] >= 0:
+                held.append(ts[r["evicted_slot"]])
+            assert len(set(held)) == 1
     assert evicted == [-1, -1, -1, 2, 3, 4]
 
 

@@ -112,6 +112,35 @@ def test_shot_reaching_into_the_window(kv):
     check_prefill_problem(res, 0, q[0], k[0], v[0], off[0].cpu().numpy(), N, N, 0.1)
 
 
+@pytest.mark.parametrize("H,Hkv,D,W,dtype", [(8, 2, 128, 32, torch.bfloat16), (4, 4, 64, 16, torch.float32),
+                                             (16, 2, 128, 32, torch.bfloat16)])
+def test_no_tail_and_a_window_as_long_as_the_prompt(kv, H, Hkv, D, W, dtype):
+    """The last shot ends at the last token (nothing after the shots, the window lies inside the last shot),
+    and prompts of exactly W and W + 1 tokens (every key row is causally masked for some query)."""
+    scale = 1.0 / math.sqrt(D)
+    N = 600
+    q, k, v, _ = _ragged_problem(2, H, Hkv, D, W, N, dtype, 17, 3, 0, 40)
+    off = torch.tensor([[0, 200, 410, N], [5, 90, 300, N]], dtype=torch.int32, device="cuda")
+    bud = torch.tensor([N, 420], dtype=torch.int32, device="cuda")
+    res = kv.prefill_compress(q, k, v, off, bud, N, scale)
+    torch.cuda.synchronize()
+    for p in range(2):
+        check_prefill_problem(res, p, q[p], k[p], v[p], off[p].cpu().numpy(), bud[p].item(), N, scale)
+    assert res.kept_count.cpu().tolist()[0] == N
+    for N in (W, W + 1):
+        q, k, v, _ = _ragged_problem(2, H, Hkv, D, W, N + 64, dtype, 18 + N, 2, 0, 40)
+        k, v = k[:, :, :N].contiguous(), v[:, :, :N].contiguous()
+        off = torch.tensor([[0, W // 3, N], [1, W // 2, N - 1]], dtype=torch.int32, device="cuda")
+        bud = torch.tensor([N, N - W // 2 + 1], dtype=torch.int32, device="cuda")
+        res = kv.prefill_compress(q, k, v, off, bud, N, scale)
+        torch.cuda.synchronize()
+        for p in range(2):
+            check_prefill_problem(res, p, q[p], k[p], v[p], off[p].cpu().numpy(), bud[p].item(), N, scale)
+    with pytest.raises(kv.ShotKVError):          # a prompt shorter than the window
+        kv.prefill_scores(q, k[:, :, : W - 1].contiguous(), torch.tensor([[0, 3], [0, 3]], dtype=torch.int32, device="cuda"),
+                          scale)
+
+
 def test_degenerate_problems_in_one_batch(kv):
     """Bad offsets, a budget smaller than the always-kept tokens, an exact fit and a zero shot budget,
     side by side with a healthy problem: each gets its own status and the others are unaffected."""
