@@ -30,6 +30,26 @@ def test_header_symbols_are_exported(lib):
         assert hasattr(lib, name), name
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 (and as C++) on its own, with no other include."""
+    import shutil
+    import subprocess
+    header = os.path.join(ROOT, "include", "shotkv.h")
+    for cc, std, lang in (("gcc", "-std=c99", "c"), ("g++", "-std=c++17", "c++")):
+        if shutil.which(cc) is None:
+            pytest.skip(f"{cc} not installed")
+        r = subprocess.run([cc, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", lang, header],
+                           capture_output=True, text=True, timeout=120)
+        assert r.returncode == 0, r.stderr
+    # a C translation unit that takes the address of every declared function links against the library's names
+    src = tmp_path / "use.c"
+    names = _declared_symbols()
+    src.write_text('#include "shotkv.h"\n' + "void* table[] = {" + ", ".join(f"(void*){n}" for n in names) + "};\n")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-Wno-pedantic", "-I", os.path.join(ROOT, "include"),
+                        "-c", str(src), "-o", str(tmp_path / "use.o")], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
+
+
 def test_host_only_entry_points(lib):
     from paper_2502_01941_amd import shotkv
     assert lib.shotkv_abi_version() == 3
